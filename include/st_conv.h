@@ -1,0 +1,138 @@
+/*
+ * st_conv.h -- C ABI of the MI355X (gfx950) zero-skipping convolution library.
+ *
+ * The library computes the three direct-convolution passes of CNN training
+ * described in SparseTrain (arXiv 1911.10175): forward (FWD), backward by
+ * input (BWI) and backward by weights (BWW).  The st_conv_{fwd,bwi,bww} entry
+ * points test one operand for zeros on the fly and skip every multiply-add
+ * that zero would feed (Sec. 3 of the paper); the st_conv_*_dense entry points
+ * compute the same tensors with no test and no skipping and serve as the
+ * dense control.  All tensors stay in a dense, fixed, blocked fp32 layout
+ * (Sec. 3 opening: the data representation is dense; Sec. 3.2.5: the lowest
+ * dimension is a channel tile).
+ *
+ * Symbols (Table 1 of the paper): N minibatch, C input channels, K output
+ * channels, H x W input height x width, R filter WIDTH (pairs with W),
+ * S filter HEIGHT (pairs with H), O = stride_w, P = stride_h.  The paper leaves
+ * padding implicit; here it is explicit and symmetric per axis.
+ *   OH = (H + 2*pad_h - S) / stride_h + 1,  OW = (W + 2*pad_w - R) / stride_w + 1.
+ *
+ * Layouts (fp32, channel block B = 16; every pointer is a DEVICE pointer,
+ * 64-byte aligned, row-major in the listed order):
+ *   activations and their gradients   x, dx : [N][C/16][H ][W ][16 c]
+ *                                      y, dy : [N][K/16][OH][OW][16 k]
+ *   filters and their gradients        w, dw : [K/16][C/16][S][R][16 c][16 k]
+ * (Sec. 3.2.5 fixes the lowest dimensions: channel tile for activations;
+ *  k vector, then c tile, then the filter-width index for filters.)
+ *
+ * Ownership and execution: the caller owns every buffer, the workspace
+ * included.  The library never allocates, frees or synchronises; each call
+ * enqueues kernels on the given HIP stream (a hipStream_t passed as void*,
+ * NULL = the default stream) and returns.  Outputs are overwritten (beta = 0).
+ * Inputs are read-only.  Buffers must not overlap.
+ *
+ * Errors: every entry point returns a status and never aborts, throws or
+ * prints.  On any status other than ST_OK nothing has been enqueued.
+ *
+ * Numerics: products and sums are fp32; the summation order is unspecified
+ * but fixed for a given shape (results are run-to-run deterministic; no
+ * floating-point atomics).  A skipped term is one whose tested factor compares
+ * equal to zero (IEEE: +0 and -0; denormals are NOT flushed before the test).
+ * With finite inputs the sparse and dense entry points agree to rounding; with
+ * non-finite inputs they may differ (0 * Inf is skipped, not NaN).
+ */
+#ifndef ST_CONV_H
+#define ST_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ST_OK = 0,
+    ST_ERR_NULL = 1,        /* a required pointer is NULL */
+    ST_ERR_BAD_SHAPE = 2,   /* non-positive dimension, C or K not a multiple of 16, empty output */
+    ST_ERR_UNSUPPORTED = 3, /* a well-formed shape that no kernel covers */
+    ST_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or smaller than st_conv_workspace_bytes */
+    ST_ERR_DEVICE = 5       /* the HIP runtime refused a launch */
+} st_status;
+
+/* Convolution geometry, Table 1 of the paper plus explicit padding. */
+typedef struct {
+    int32_t N, C, K;
+    int32_t H, W;               /* input height, width */
+    int32_t R, S;               /* filter width (u), filter height (v) */
+    int32_t stride_w, stride_h; /* O, P */
+    int32_t pad_w, pad_h;       /* zeros added on each side of W / of H */
+} st_conv_desc;
+
+enum { ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2 };
+
+/*
+ * FWD, Eq. (1) of Sec. 2.1 (correlation, filter not flipped, no bias):
+ *   y[n,k,oh,ow] = sum_{c,v,u} x[n,c,oh*P-pad_h+v, ow*O-pad_w+u] * w[k,c,v,u]
+ * with reads outside the image equal to 0.  st_conv_fwd skips all products of
+ * an x element that is zero (Sec. 3.1-3.2, Alg. 1-3).
+ *   x  in   [N][C/16][H][W][16]           w  in  [K/16][C/16][S][R][16][16]
+ *   y  out  [N][K/16][OH][OW][16]
+ *   ws / ws_bytes: workspace of at least st_conv_workspace_bytes(desc, ST_PASS_FWD, dense)
+ *                  bytes (may be NULL when that is 0).
+ */
+st_status st_conv_fwd(const st_conv_desc *desc, const float *x, const float *w, float *y,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+st_status st_conv_fwd_dense(const st_conv_desc *desc, const float *x, const float *w, float *y,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * BWI, Sec. 2.1 (passage after Eq. (2)) and Sec. 3.3: the gradient of the loss
+ * w.r.t. the layer input is the correlation of dy with the transposed filters:
+ *   dx[n,c,ih,iw] = sum_{k,v,u} dy[n,k,oh,ow] * w[k,c,v,u]
+ *   over the (oh,ow) with oh*P-pad_h+v = ih and ow*O-pad_w+u = iw.
+ * st_conv_bwi skips all products of a dy element that is zero.
+ *   dy in   [N][K/16][OH][OW][16]         w  in  [K/16][C/16][S][R][16][16]
+ *   dx out  [N][C/16][H][W][16]
+ */
+st_status st_conv_bwi(const st_conv_desc *desc, const float *dy, const float *w, float *dx,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+st_status st_conv_bwi_dense(const st_conv_desc *desc, const float *dy, const float *w, float *dx,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * BWW, Sec. 2.1 (same passage) and Sec. 3.4 (Alg. 4-5): the gradient w.r.t.
+ * the filters is the correlation of the input with dy:
+ *   dw[k,c,v,u] = sum_{n,oh,ow} x[n,c,oh*P-pad_h+v, ow*O-pad_w+u] * dy[n,k,oh,ow].
+ * st_conv_bww skips all products of an x element that is zero (the operand
+ * Alg. 4 tests).  Partial sums over parts of the minibatch are kept in the
+ * workspace and added by a second kernel in a fixed order (Sec. 3.4, last
+ * paragraphs: partial results are accumulated at the end of a sweep).
+ *   x  in   [N][C/16][H][W][16]           dy in  [N][K/16][OH][OW][16]
+ *   dw out  [K/16][C/16][S][R][16][16]
+ */
+st_status st_conv_bww(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
+                      void *ws, size_t ws_bytes, void *hip_stream);
+st_status st_conv_bww_dense(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Bytes of device workspace the given pass needs for this geometry
+ * (pass = ST_PASS_*, dense = 0 for st_conv_<pass>, 1 for st_conv_<pass>_dense).
+ * Returns 0 when none is needed or when desc is invalid (the pass itself then
+ * reports the error).  The workspace must be 256-byte aligned.  Its contents
+ * need not be initialised and are undefined afterwards; two calls that are in
+ * flight at the same time must not share one.
+ */
+size_t st_conv_workspace_bytes(const st_conv_desc *desc, int pass, int dense);
+
+/* Static, NUL-terminated description of a status value. */
+const char *st_status_str(st_status status);
+
+/* Library version, "major.minor". */
+const char *st_conv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ST_CONV_H */

@@ -1,0 +1,57 @@
+// Shared declarations of the gfx950 convolution library (internal; the public
+// interface is include/st_conv.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "st_conv.h"
+
+namespace st {
+
+constexpr int kBlk = 16;        // channel block of the blocked layouts
+constexpr int kWave = 64;       // CDNA wavefront width
+
+// Geometry of one correlation "act_out[n,ko,oh,ow] = sum act_in[n,ci,oh*P-ph+v,ow*O-pw+u] * f[ko,ci,v,u]".
+// FWD uses it directly; stride-1 BWI is the same correlation on dy with transposed, tap-reversed
+// filters (SparseTrain Sec. 3.3), so both passes share this struct and the kernels built on it.
+struct Geom {
+    int N;
+    int Ci, Ko;          // reduced (input) channels, produced (output) channels
+    int Hi, Wi;          // spatial size of the input activation
+    int Ho, Wo;          // spatial size of the output activation
+    int R, S;            // filter width, height
+    int sw, sh;          // strides
+    int pw, ph;          // padding
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---- launchers (each returns hipSuccess or the launch error) -------------------------------
+// generic kernels: any geometry the API accepts
+hipError_t launch_generic_fwd(const st_conv_desc &d, const float *x, const float *w, float *y,
+                              bool sparse, hipStream_t s);
+hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const float *w, float *dx,
+                              bool sparse, hipStream_t s);
+hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                              bool sparse, hipStream_t s);
+
+// filter transposition for stride-1 BWI: wt[C/16][K/16][S][R][16 k][16 c] with taps reversed
+hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s);
+
+// unit-stride fast paths
+bool fwd_sparse_supported(const Geom &g);
+hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s);
+bool fwd_dense_supported(const Geom &g);
+hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *f, float *out, hipStream_t s);
+
+bool bww_fast_supported(const st_conv_desc &d);
+size_t bww_sparse_workspace(const st_conv_desc &d);
+hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                             float *ws, hipStream_t s);
+size_t bww_dense_workspace(const st_conv_desc &d);
+hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                            float *ws, hipStream_t s);
+
+}  // namespace st

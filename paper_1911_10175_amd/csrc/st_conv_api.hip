@@ -1,0 +1,202 @@
+// C ABI of the library (include/st_conv.h): argument validation and kernel selection.
+// No allocation, no synchronisation, no printing happens here.
+#include "st_common.hpp"
+
+namespace {
+
+using st::Geom;
+
+struct Dims {
+    int OH, OW;
+};
+
+st_status validate(const st_conv_desc *d, Dims *o)
+{
+    if (!d) return ST_ERR_NULL;
+    if (d->N <= 0 || d->C <= 0 || d->K <= 0 || d->H <= 0 || d->W <= 0) return ST_ERR_BAD_SHAPE;
+    if (d->R <= 0 || d->S <= 0 || d->stride_w <= 0 || d->stride_h <= 0) return ST_ERR_BAD_SHAPE;
+    if (d->pad_w < 0 || d->pad_h < 0) return ST_ERR_BAD_SHAPE;
+    if (d->C % st::kBlk || d->K % st::kBlk) return ST_ERR_BAD_SHAPE;
+    if (d->H + 2 * d->pad_h < d->S || d->W + 2 * d->pad_w < d->R) return ST_ERR_BAD_SHAPE;
+    o->OH = (d->H + 2 * d->pad_h - d->S) / d->stride_h + 1;
+    o->OW = (d->W + 2 * d->pad_w - d->R) / d->stride_w + 1;
+    // the kernels index tensors with size_t but keep per-image pixel counts and grids in int
+    const long long lim = 0x7fffffffLL;
+    if ((long long)d->H * d->W > lim || (long long)o->OH * o->OW > lim) return ST_ERR_UNSUPPORTED;
+    if ((long long)d->C * d->S * d->R > lim || d->N > 65535) return ST_ERR_UNSUPPORTED;
+    // padding at least as large as the filter would make whole output rows read only zeros;
+    // legal, handled by the generic kernels
+    return ST_OK;
+}
+
+Geom fwd_geom(const st_conv_desc &d, const Dims &o)
+{
+    Geom g;
+    g.N = d.N; g.Ci = d.C; g.Ko = d.K;
+    g.Hi = d.H; g.Wi = d.W; g.Ho = o.OH; g.Wo = o.OW;
+    g.R = d.R; g.S = d.S; g.sw = d.stride_w; g.sh = d.stride_h; g.pw = d.pad_w; g.ph = d.pad_h;
+    return g;
+}
+
+// Unit-stride BWI as a correlation of dy with transposed, tap-reversed filters
+// (SparseTrain Sec. 3.3): input = dy [N][K][OH][OW], output = dx [N][C][H][W],
+// padding S-1-pad_h / R-1-pad_w.
+bool bwi_as_fwd(const st_conv_desc &d, const Dims &o, Geom *g)
+{
+    if (d.stride_w != 1 || d.stride_h != 1) return false;
+    if (d.pad_w > d.R - 1 || d.pad_h > d.S - 1) return false;
+    g->N = d.N; g->Ci = d.K; g->Ko = d.C;
+    g->Hi = o.OH; g->Wi = o.OW; g->Ho = d.H; g->Wo = d.W;
+    g->R = d.R; g->S = d.S; g->sw = 1; g->sh = 1;
+    g->pw = d.R - 1 - d.pad_w; g->ph = d.S - 1 - d.pad_h;
+    return true;
+}
+
+size_t filter_bytes(const st_conv_desc &d)
+{
+    return (size_t)d.K * d.C * d.S * d.R * sizeof(float);
+}
+
+bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return true;
+    return ws != nullptr && have >= need && ((uintptr_t)ws % 256) == 0;
+}
+
+st_status dev(hipError_t e) { return e == hipSuccess ? ST_OK : ST_ERR_DEVICE; }
+
+size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dense)
+{
+    switch (pass) {
+    case ST_PASS_FWD:
+        return 0;
+    case ST_PASS_BWI: {
+        Geom g;
+        if (!bwi_as_fwd(d, o, &g)) return 0;
+        const bool fast = dense ? st::fwd_dense_supported(g) : st::fwd_sparse_supported(g);
+        return fast ? filter_bytes(d) : 0;
+    }
+    case ST_PASS_BWW:
+        if (!st::bww_fast_supported(d)) return 0;
+        return dense ? st::bww_dense_workspace(d) : st::bww_sparse_workspace(d);
+    default:
+        return 0;
+    }
+}
+
+st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *y, void *ws,
+                  size_t ws_bytes, void *stream, bool dense)
+{
+    (void)ws; (void)ws_bytes;
+    Dims o;
+    st_status rc = validate(d, &o);
+    if (rc != ST_OK) return rc;
+    if (!x || !w || !y) return ST_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Geom g = fwd_geom(*d, o);
+    if (dense) {
+        if (st::fwd_dense_supported(g)) return dev(st::launch_fwd_dense(g, x, w, y, s));
+        return dev(st::launch_generic_fwd(*d, x, w, y, false, s));
+    }
+    if (st::fwd_sparse_supported(g)) return dev(st::launch_fwd_sparse(g, x, w, y, s));
+    return dev(st::launch_generic_fwd(*d, x, w, y, true, s));
+}
+
+st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,
+                  size_t ws_bytes, void *stream, bool dense)
+{
+    Dims o;
+    st_status rc = validate(d, &o);
+    if (rc != ST_OK) return rc;
+    if (!dy || !w || !dx) return ST_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Geom g;
+    const bool fast = bwi_as_fwd(*d, o, &g) &&
+                      (dense ? st::fwd_dense_supported(g) : st::fwd_sparse_supported(g));
+    if (!fast) return dev(st::launch_generic_bwi(*d, dy, w, dx, !dense, s));
+    if (!ws_ok(ws, ws_bytes, filter_bytes(*d))) return ST_ERR_WORKSPACE;
+    float *wt = static_cast<float *>(ws);
+    hipError_t e = st::launch_transpose_filters(*d, w, wt, s);
+    if (e != hipSuccess) return ST_ERR_DEVICE;
+    return dev(dense ? st::launch_fwd_dense(g, dy, wt, dx, s) : st::launch_fwd_sparse(g, dy, wt, dx, s));
+}
+
+st_status run_bww(const st_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
+                  size_t ws_bytes, void *stream, bool dense)
+{
+    Dims o;
+    st_status rc = validate(d, &o);
+    if (rc != ST_OK) return rc;
+    if (!x || !dy || !dw) return ST_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!st::bww_fast_supported(*d)) return dev(st::launch_generic_bww(*d, x, dy, dw, !dense, s));
+    const size_t need = dense ? st::bww_dense_workspace(*d) : st::bww_sparse_workspace(*d);
+    if (!ws_ok(ws, ws_bytes, need)) return ST_ERR_WORKSPACE;
+    float *wsf = static_cast<float *>(ws);
+    return dev(dense ? st::launch_bww_dense(*d, x, dy, dw, wsf, s)
+                     : st::launch_bww_sparse(*d, x, dy, dw, wsf, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+st_status st_conv_fwd(const st_conv_desc *desc, const float *x, const float *w, float *y, void *ws,
+                      size_t ws_bytes, void *hip_stream)
+{
+    return run_fwd(desc, x, w, y, ws, ws_bytes, hip_stream, false);
+}
+
+st_status st_conv_fwd_dense(const st_conv_desc *desc, const float *x, const float *w, float *y,
+                            void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return run_fwd(desc, x, w, y, ws, ws_bytes, hip_stream, true);
+}
+
+st_status st_conv_bwi(const st_conv_desc *desc, const float *dy, const float *w, float *dx, void *ws,
+                      size_t ws_bytes, void *hip_stream)
+{
+    return run_bwi(desc, dy, w, dx, ws, ws_bytes, hip_stream, false);
+}
+
+st_status st_conv_bwi_dense(const st_conv_desc *desc, const float *dy, const float *w, float *dx,
+                            void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return run_bwi(desc, dy, w, dx, ws, ws_bytes, hip_stream, true);
+}
+
+st_status st_conv_bww(const st_conv_desc *desc, const float *x, const float *dy, float *dw, void *ws,
+                      size_t ws_bytes, void *hip_stream)
+{
+    return run_bww(desc, x, dy, dw, ws, ws_bytes, hip_stream, false);
+}
+
+st_status st_conv_bww_dense(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
+                            void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return run_bww(desc, x, dy, dw, ws, ws_bytes, hip_stream, true);
+}
+
+size_t st_conv_workspace_bytes(const st_conv_desc *desc, int pass, int dense)
+{
+    Dims o;
+    if (validate(desc, &o) != ST_OK) return 0;
+    return workspace_bytes(*desc, o, pass, dense != 0);
+}
+
+const char *st_status_str(st_status status)
+{
+    switch (status) {
+    case ST_OK: return "ok";
+    case ST_ERR_NULL: return "a required pointer is NULL";
+    case ST_ERR_BAD_SHAPE: return "bad shape: non-positive dimension, C or K not a multiple of 16, or empty output";
+    case ST_ERR_UNSUPPORTED: return "shape not supported by any kernel";
+    case ST_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ST_ERR_DEVICE: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+const char *st_conv_version(void) { return "0.1"; }
+
+}  // extern "C"

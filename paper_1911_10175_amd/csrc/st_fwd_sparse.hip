@@ -1,0 +1,217 @@
+// Zero-skipping unit-stride correlation for FWD and (with transposed filters) BWI.
+//
+// Mapping of the paper's method (SparseTrain Sec. 3.1-3.2) onto a CDNA wavefront:
+//  * The vectorised dimension is the output channel (Sec. 3.1): one lane owns KPL output
+//    channels, a wavefront owns 64*KPL of them.
+//  * The output tile (TH x TW pixels per channel) stays in registers for the whole reduction
+//    over input channels and taps, the register-resident output buffer of Sec. 3.2.3 extended
+//    from a row segment to a 2-D tile (a wavefront has 64*KPL*TH*TW accumulators, not 30).
+//  * The tested operand is one input element shared by every lane.  For one input channel the
+//    (TH+S-1) x (TW+R-1) input pixels that reach the tile are held one per lane; a single
+//    v_cmp over them yields the 64-bit non-zero mask (the vector compare of Alg. 3, vectorised
+//    over pixels instead of channels), and each set bit leads to one lane broadcast plus the up
+//    to R*S*KPL multiply-adds of that element (T of Sec. 3.1).  A clear bit is a scalar branch
+//    over all of them, taken by the whole wavefront, so no lane ever idles on a zero.
+//  * Filters for the current input channel (R*S*KPL values per lane) sit in registers and are
+//    reused by every non-zero pixel of the tile; they stream from L2, 64 B per 16 lanes.
+#include <type_traits>
+
+#include "st_common.hpp"
+
+namespace st {
+namespace {
+
+__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
+{
+    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+template <int R, int S, int TH, int TW, int KPL>
+struct FwdSparseCfg {
+    static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
+    static constexpr int NXV = (HP + 63) / 64;              // registers holding one channel of the halo
+    static constexpr int PST = ((HP + 7) / 8) * 8 + 4;      // LDS pixel stride, = 4 (mod 8)
+    static constexpr int WAVES = 4;
+    static constexpr int KT = 64 * KPL;                     // output channels per wavefront
+};
+
+template <int R, int S, int TH, int TW, int KPL>
+__global__ __launch_bounds__(256) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
+                                                         const float *__restrict__ f,
+                                                         float *__restrict__ out,
+                                                         int tiles_w, int tiles_h, int ktiles, int total)
+{
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
+    constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
+    __shared__ float lds_all[Cfg::WAVES][kBlk * PST];
+
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int wid = blockIdx.x * Cfg::WAVES + wave;
+    if (wid >= total) return;                       // whole wavefront leaves; no block barrier is used
+    float *lds = lds_all[wave];
+
+    int t = wid;
+    const int kt = t % ktiles; t /= ktiles;
+    const int tw = t % tiles_w; t /= tiles_w;
+    const int th = t % tiles_h;
+    const int n = t / tiles_h;
+    const int oh0 = th * TH, ow0 = tw * TW;
+    const int ih0 = oh0 - g.ph, iw0 = ow0 - g.pw;
+    const int CiB = g.Ci / kBlk, KoB = g.Ko / kBlk;
+
+    float acc[KPL][TH * TW];
+#pragma unroll
+    for (int j = 0; j < KPL; ++j)
+#pragma unroll
+        for (int i = 0; i < TH * TW; ++i) acc[j][i] = 0.f;
+
+    // filter pointer of this lane's channel(s): element [kb][cb][v][u][ci][ki]
+    const float *fp[KPL];
+    bool kact[KPL];
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) {
+        const int k = kt * Cfg::KT + j * kWave + lane;
+        kact[j] = k < g.Ko;
+        const int kb = kact[j] ? k / kBlk : 0;
+        fp[j] = f + (size_t)kb * CiB * (S * R * kBlk * kBlk) + (k % kBlk);
+    }
+
+    for (int cb = 0; cb < CiB; ++cb) {
+        // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int jj = 0; jj < (HP * 4 + 63) / 64; ++jj) {
+            const int idx = jj * kWave + lane;
+            const int pix = idx >> 2, q = idx & 3;
+            if (pix < HP) {
+                const int a = pix / HW, b = pix % HW;
+                const int ih = ih0 + a, iw = iw0 + b;
+                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi)
+                    val = *reinterpret_cast<const float4 *>(in + act_off(n, cb, ih, iw, CiB, g.Hi, g.Wi) + q * 4);
+                lds[(q * 4 + 0) * PST + pix] = val.x;
+                lds[(q * 4 + 1) * PST + pix] = val.y;
+                lds[(q * 4 + 2) * PST + pix] = val.z;
+                lds[(q * 4 + 3) * PST + pix] = val.w;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        const float *fcb[KPL];
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) fcb[j] = fp[j] + (size_t)cb * (S * R * kBlk * kBlk);
+
+        for (int ci = 0; ci < kBlk; ++ci) {
+            // one channel of the halo, one pixel per lane
+            float xv[NXV];
+            unsigned m32[2 * NXV];
+#pragma unroll
+            for (int j = 0; j < NXV; ++j) {
+                const int pix = j * kWave + lane;
+                xv[j] = (pix < HP) ? lds[ci * PST + pix] : 0.f;
+                const unsigned long long m = __builtin_amdgcn_ballot_w64(xv[j] != 0.f);
+                m32[2 * j] = (unsigned)m;
+                m32[2 * j + 1] = (unsigned)(m >> 32);
+            }
+            // filters of this input channel
+            float wv[KPL][S * R];
+#pragma unroll
+            for (int j = 0; j < KPL; ++j)
+#pragma unroll
+                for (int tp = 0; tp < S * R; ++tp)
+                    wv[j][tp] = fcb[j][tp * (kBlk * kBlk) + ci * kBlk];
+
+            // one branch per halo pixel; all register indices below are compile-time constants
+            static_for<0, HP>([&](auto I) __attribute__((always_inline)) {
+                constexpr int i = decltype(I)::value;
+                constexpr int a = i / HW, b = i % HW;
+                if (m32[i / 32] & (1u << (i % 32))) {
+                    const float xs = __int_as_float(
+                        __builtin_amdgcn_readlane(__float_as_int(xv[i / 64]), i % 64));
+#pragma unroll
+                    for (int v = 0; v < S; ++v) {
+                        const int ol = a - v;
+                        if (ol < 0 || ol >= TH) continue;
+#pragma unroll
+                        for (int u = 0; u < R; ++u) {
+                            const int oc = b - u;
+                            if (oc < 0 || oc >= TW) continue;
+#pragma unroll
+                            for (int j = 0; j < KPL; ++j)
+                                acc[j][ol * TW + oc] = fmaf(xs, wv[j][v * R + u], acc[j][ol * TW + oc]);
+                        }
+                    }
+                }
+            });
+        }
+    }
+
+    // ---- store the tile ----
+#pragma unroll
+    for (int j = 0; j < KPL; ++j) {
+        if (!kact[j]) continue;
+        const int k = kt * Cfg::KT + j * kWave + lane;
+        const int kb = k / kBlk, ki = k % kBlk;
+#pragma unroll
+        for (int a = 0; a < TH; ++a) {
+            const int oh = oh0 + a;
+            if (oh >= g.Ho) continue;
+#pragma unroll
+            for (int b = 0; b < TW; ++b) {
+                const int ow = ow0 + b;
+                if (ow >= g.Wo) continue;
+                out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[j][a * TW + b];
+            }
+        }
+    }
+}
+
+template <int R, int S, int TH, int TW, int KPL>
+hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+{
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
+    const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
+    const int ktiles = ceil_div(g.Ko, Cfg::KT);
+    const long long total = (long long)tiles_w * tiles_h * ktiles * g.N;
+    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((total + Cfg::WAVES - 1) / Cfg::WAVES));
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL>), grid, dim3(256), 0, s, g, in, f, out,
+                       tiles_w, tiles_h, ktiles, (int)total);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool fwd_sparse_supported(const Geom &g)
+{
+    if (g.sw != 1 || g.sh != 1) return false;
+    if (g.R == 3 && g.S == 3) return g.pw <= 2 && g.ph <= 2;
+    if (g.R == 1 && g.S == 1) return g.pw == 0 && g.ph == 0;
+    return false;
+}
+
+hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+{
+    if (g.R == 3 && g.S == 3) {
+        if (g.Ko % 128 == 0) return launch_cfg<3, 3, 8, 8, 2>(g, in, f, out, s);
+        return launch_cfg<3, 3, 8, 8, 1>(g, in, f, out, s);
+    }
+    if (g.R == 1 && g.S == 1) {
+        if (g.Ko % 128 == 0) return launch_cfg<1, 1, 8, 8, 2>(g, in, f, out, s);
+        return launch_cfg<1, 1, 8, 8, 1>(g, in, f, out, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace st

@@ -1,0 +1,203 @@
+// Generic kernels: every geometry the API accepts (any stride, padding, filter size).
+//
+// They are the fall-back for shapes the tiled unit-stride kernels do not cover.  One wavefront
+// owns one output location and up to 64 channels of the vectorised dimension (one channel per
+// lane), so the tested operand is a single value shared by the whole wavefront: the zero test
+// is a scalar compare and a taken branch skips the multiply-add for all lanes at once.  This is
+// the direct analogue of the paper's broadcast-scalar times channel-vector FMA with the zero
+// test in front of it (SparseTrain Sec. 3.1, Alg. 1; Sec. 3.4, Alg. 4), written per output
+// (gather form) so that no two wavefronts update the same element.
+#include "st_common.hpp"
+
+namespace st {
+namespace {
+
+__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
+{
+    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
+}
+
+__device__ __forceinline__ size_t flt_off(int kb, int cb, int v, int u, int CB, int S, int R)
+{
+    return ((((size_t)kb * CB + cb) * S + v) * R + u) * (kBlk * kBlk);
+}
+
+// y[n,k,oh,ow] for k = 64*blockIdx.y + lane
+template <bool SPARSE>
+__global__ __launch_bounds__(64) void generic_fwd_kernel(st_conv_desc d, int OH, int OW,
+                                                         const float *__restrict__ x,
+                                                         const float *__restrict__ w,
+                                                         float *__restrict__ y)
+{
+    const int lane = threadIdx.x;
+    const int k = blockIdx.y * kWave + lane;
+    const int ow = blockIdx.x % OW, oh = blockIdx.x / OW, n = blockIdx.z;
+    const int CB = d.C / kBlk;
+    const bool active = k < d.K;
+    const int kb = active ? k / kBlk : 0, ki = k % kBlk;
+    float acc = 0.f;
+    for (int v = 0; v < d.S; ++v) {
+        const int ih = oh * d.stride_h - d.pad_h + v;
+        if (ih < 0 || ih >= d.H) continue;
+        for (int u = 0; u < d.R; ++u) {
+            const int iw = ow * d.stride_w - d.pad_w + u;
+            if (iw < 0 || iw >= d.W) continue;
+            for (int cb = 0; cb < CB; ++cb) {
+                const float *xp = x + act_off(n, cb, ih, iw, CB, d.H, d.W);
+                const float *wp = w + flt_off(kb, cb, v, u, CB, d.S, d.R) + ki;
+                for (int ci = 0; ci < kBlk; ++ci) {
+                    const float xv = xp[ci];            // same address in every lane
+                    if (SPARSE && !(xv != 0.f)) continue;
+                    acc = fmaf(xv, wp[ci * kBlk], acc);
+                }
+            }
+        }
+    }
+    if (active) y[act_off(n, kb, oh, ow, d.K / kBlk, OH, OW) + ki] = acc;
+}
+
+// dx[n,c,ih,iw] for c = 64*blockIdx.y + lane
+template <bool SPARSE>
+__global__ __launch_bounds__(64) void generic_bwi_kernel(st_conv_desc d, int OH, int OW,
+                                                         const float *__restrict__ dy,
+                                                         const float *__restrict__ w,
+                                                         float *__restrict__ dx)
+{
+    const int lane = threadIdx.x;
+    const int c = blockIdx.y * kWave + lane;
+    const int iw = blockIdx.x % d.W, ih = blockIdx.x / d.W, n = blockIdx.z;
+    const int CB = d.C / kBlk, KB = d.K / kBlk;
+    const bool active = c < d.C;
+    const int cb = active ? c / kBlk : 0, ci = c % kBlk;
+    float acc = 0.f;
+    for (int v = 0; v < d.S; ++v) {
+        const int th = ih + d.pad_h - v;
+        if (th < 0 || th % d.stride_h) continue;
+        const int oh = th / d.stride_h;
+        if (oh >= OH) continue;
+        for (int u = 0; u < d.R; ++u) {
+            const int tw = iw + d.pad_w - u;
+            if (tw < 0 || tw % d.stride_w) continue;
+            const int ow = tw / d.stride_w;
+            if (ow >= OW) continue;
+            for (int kb = 0; kb < KB; ++kb) {
+                const float *gp = dy + act_off(n, kb, oh, ow, KB, OH, OW);
+                const float *wp = w + flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk;
+                for (int ki = 0; ki < kBlk; ++ki) {
+                    const float gv = gp[ki];
+                    if (SPARSE && !(gv != 0.f)) continue;
+                    acc = fmaf(gv, wp[ki], acc);
+                }
+            }
+        }
+    }
+    if (active) dx[act_off(n, cb, ih, iw, CB, d.H, d.W) + ci] = acc;
+}
+
+// dw[k,c,v,u] for k = 64*blockIdx.y + lane, (c,v,u) from blockIdx.x
+template <bool SPARSE>
+__global__ __launch_bounds__(64) void generic_bww_kernel(st_conv_desc d, int OH, int OW,
+                                                         const float *__restrict__ x,
+                                                         const float *__restrict__ dy,
+                                                         float *__restrict__ dw)
+{
+    const int lane = threadIdx.x;
+    const int k = blockIdx.y * kWave + lane;
+    int t = blockIdx.x;
+    const int u = t % d.R; t /= d.R;
+    const int v = t % d.S; t /= d.S;
+    const int c = t;
+    const int CB = d.C / kBlk, KB = d.K / kBlk;
+    const bool active = k < d.K;
+    const int kb = active ? k / kBlk : 0, ki = k % kBlk;
+    const int cb = c / kBlk, ci = c % kBlk;
+    float acc = 0.f;
+    for (int n = 0; n < d.N; ++n)
+        for (int oh = 0; oh < OH; ++oh) {
+            const int ih = oh * d.stride_h - d.pad_h + v;
+            if (ih < 0 || ih >= d.H) continue;
+            for (int ow = 0; ow < OW; ++ow) {
+                const int iw = ow * d.stride_w - d.pad_w + u;
+                if (iw < 0 || iw >= d.W) continue;
+                const float xv = x[act_off(n, cb, ih, iw, CB, d.H, d.W) + ci];
+                if (SPARSE && !(xv != 0.f)) continue;
+                acc = fmaf(xv, dy[act_off(n, kb, oh, ow, KB, OH, OW) + ki], acc);
+            }
+        }
+    if (active) dw[flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk + ki] = acc;
+}
+
+// wt[cb][kb][S-1-v][R-1-u][ki][ci] = w[kb][cb][v][u][ci][ki]
+__global__ __launch_bounds__(256) void transpose_filters_kernel(int KB, int CB, int S, int R,
+                                                                const float *__restrict__ w,
+                                                                float *__restrict__ wt)
+{
+    __shared__ float tile[kBlk][kBlk + 1];
+    int t = blockIdx.x;
+    const int u = t % R; t /= R;
+    const int v = t % S; t /= S;
+    const int cb = t % CB;
+    const int kb = t / CB;
+    const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
+    tile[a][b] = w[flt_off(kb, cb, v, u, CB, S, R) + a * kBlk + b];      // a = ci, b = ki
+    __syncthreads();
+    // destination block [cb][kb][S-1-v][R-1-u], element [ki = a][ci = b]
+    wt[flt_off(cb, kb, S - 1 - v, R - 1 - u, KB, S, R) + a * kBlk + b] = tile[b][a];
+}
+
+inline void out_dims(const st_conv_desc &d, int &OH, int &OW)
+{
+    OH = (d.H + 2 * d.pad_h - d.S) / d.stride_h + 1;
+    OW = (d.W + 2 * d.pad_w - d.R) / d.stride_w + 1;
+}
+
+}  // namespace
+
+hipError_t launch_generic_fwd(const st_conv_desc &d, const float *x, const float *w, float *y,
+                              bool sparse, hipStream_t s)
+{
+    int OH, OW;
+    out_dims(d, OH, OW);
+    dim3 grid(OH * OW, ceil_div(d.K, kWave), d.N);
+    if (sparse)
+        hipLaunchKernelGGL(generic_fwd_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, w, y);
+    else
+        hipLaunchKernelGGL(generic_fwd_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, w, y);
+    return hipGetLastError();
+}
+
+hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const float *w, float *dx,
+                              bool sparse, hipStream_t s)
+{
+    int OH, OW;
+    out_dims(d, OH, OW);
+    dim3 grid(d.H * d.W, ceil_div(d.C, kWave), d.N);
+    if (sparse)
+        hipLaunchKernelGGL(generic_bwi_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, dy, w, dx);
+    else
+        hipLaunchKernelGGL(generic_bwi_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, dy, w, dx);
+    return hipGetLastError();
+}
+
+hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                              bool sparse, hipStream_t s)
+{
+    int OH, OW;
+    out_dims(d, OH, OW);
+    dim3 grid(d.C * d.S * d.R, ceil_div(d.K, kWave), 1);
+    if (sparse)
+        hipLaunchKernelGGL(generic_bww_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
+    else
+        hipLaunchKernelGGL(generic_bww_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s)
+{
+    const int KB = d.K / kBlk, CB = d.C / kBlk;
+    dim3 grid(KB * CB * d.S * d.R);
+    hipLaunchKernelGGL(transpose_filters_kernel, grid, dim3(256), 0, s, KB, CB, d.S, d.R, w, wt);
+    return hipGetLastError();
+}
+
+}  // namespace st

@@ -1,0 +1,83 @@
+"""Host-side checks of the C ABI: the library loads without a GPU, exports every symbol the
+public header declares, and validates arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1911_10175_amd as st
+from paper_1911_10175_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "st_conv.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(st_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = st.load_library()
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings_and_version():
+    assert st.st_status_str(0) == "ok"
+    seen = {st.st_status_str(i) for i in range(6)}
+    assert len(seen) == 6 and all(seen)
+    assert st.st_status_str(99) == "unknown status"
+    assert re.fullmatch(r"\d+\.\d+", st.st_conv_version())
+
+
+def test_validation_happens_on_the_host():
+    good = st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 1, 1, 1, 1)
+    lib = st.load_library()
+    # NULL descriptor
+    assert lib.st_conv_fwd(None, None, None, None, None, 0, None) == 1
+    # NULL tensors
+    assert st.st_conv_fwd(good, None, None, None, check=False) == 1
+    assert st.st_conv_bwi_dense(good, None, None, None, check=False) == 1
+    assert st.st_conv_bww(good, None, None, None, check=False) == 1
+    bad = [st.ConvDesc(0, 16, 16, 8, 8, 3, 3), st.ConvDesc(1, 8, 16, 8, 8, 3, 3, 1, 1, 1, 1),
+           st.ConvDesc(1, 16, 24, 8, 8, 3, 3, 1, 1, 1, 1), st.ConvDesc(1, 16, 16, 2, 8, 3, 3),
+           st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 0, 1), st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 1, 1, -1, 0)]
+    for d in bad:
+        for fn in (st.st_conv_fwd, st.st_conv_fwd_dense, st.st_conv_bwi, st.st_conv_bwi_dense,
+                   st.st_conv_bww, st.st_conv_bww_dense):
+            assert fn(d, 256, 256, 256, check=False) == 2, d
+        assert st.st_conv_workspace_bytes(d, st.ST_PASS_BWI) == 0
+    with pytest.raises(st.StConvError) as e:
+        st.st_conv_fwd(bad[0], 256, 256, 256)
+    assert e.value.status == 2
+
+
+def test_workspace_query_and_rejection():
+    d = st.ConvDesc(16, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_workspace_bytes(d, st.ST_PASS_FWD) == 0
+    for dense in (False, True):
+        need = st.st_conv_workspace_bytes(d, st.ST_PASS_BWI, dense)
+        if need:
+            fn = st.st_conv_bwi_dense if dense else st.st_conv_bwi
+            # missing, too small and misaligned workspaces are refused before any launch
+            assert fn(d, 256, 256, 256, ws=None, check=False) == 4
+            assert fn(d, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
+            assert fn(d, 256, 256, 256, ws=4096 + 64, ws_bytes=need, check=False) == 4
+        need = st.st_conv_workspace_bytes(d, st.ST_PASS_BWW, dense)
+        if need:
+            fn = st.st_conv_bww_dense if dense else st.st_conv_bww
+            assert fn(d, 256, 256, 256, ws=None, check=False) == 4
+            assert fn(d, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
+    assert st.st_conv_workspace_bytes(d, 7) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_HERE", str(tmp_path))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()

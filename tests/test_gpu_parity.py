@@ -1,0 +1,159 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Every test here needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import stgen
+from oracle import st_ref
+from oracle.st_ref import Geom
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from tests.gpu_harness import (DeviceLayer, assert_close, check_all_passes_full,
+                                   check_all_passes_sampled, desc_of)
+    import paper_1911_10175_amd as st
+
+
+def geom_of(layer: stgen.Layer) -> Geom:
+    return Geom(layer.N, layer.C, layer.K, layer.H, layer.W, layer.R, layer.S,
+                layer.stride, layer.stride, layer.pad, layer.pad)
+
+
+def synth(g: Geom, p_x, p_dy, seed):
+    x = stgen.relu_sparse(g.x_shape, p_x, 4 * seed)
+    w = stgen.he_normal(g.w_shape, 4 * seed + 1)
+    dy = stgen.bernoulli_masked(g.y_shape, p_dy, 4 * seed + 2, 4 * seed + 3)
+    return x, w, dy
+
+
+def test_library_is_the_hip_build():
+    assert st.lib_path().endswith("libst_conv.so")
+    assert st.st_conv_version()
+
+
+def test_config1_tiny_layer():
+    """N=1, C=K=16, 8x8, 3x3 pad 1, x 50 % zeros, dy = g * (FWD output > 0), seed 0."""
+    L = stgen.TINY
+    g = geom_of(L)
+    x, w, _ = stgen.make_layer_tensors(L, seed=0)
+    y_ref, _ = st_ref.conv_fwd(g, x, w)
+    dy = stgen.relu_grad(y_ref.astype(np.float32), 2)
+    assert 0.3 < stgen.zero_fraction(x) < 0.7 and 0.2 < stgen.zero_fraction(dy) < 0.8
+    check_all_passes_full(g, x, w, dy, "config1")
+
+
+SMALL = [
+    # several 8x8 tiles with a ragged tail in both directions
+    ("3x3_ragged", Geom(2, 32, 64, 13, 19, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    # 128 output channels per wavefront, 3 channel blocks
+    ("3x3_k128", Geom(2, 48, 128, 20, 20, 3, 3, 1, 1, 1, 1), 0.6, 0.45),
+    ("3x3_k256_c64", Geom(1, 64, 256, 9, 17, 3, 3, 1, 1, 1, 1), 0.3, 0.7),
+    # fewer channels than lanes
+    ("3x3_k16", Geom(3, 16, 16, 10, 7, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    ("3x3_k48_c80", Geom(1, 80, 48, 11, 12, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    # other paddings of the 3x3 fast path
+    ("3x3_pad0", Geom(2, 32, 64, 12, 14, 3, 3, 1, 1, 0, 0), 0.5, 0.5),
+    ("3x3_pad2_1", Geom(1, 32, 64, 9, 10, 3, 3, 1, 1, 2, 1), 0.5, 0.5),
+    # 1x1
+    ("1x1_k128", Geom(2, 64, 128, 12, 12, 1, 1), 0.4, 0.5),
+    ("1x1_k64", Geom(2, 256, 64, 9, 11, 1, 1), 0.55, 0.5),
+    # shapes only the generic kernels cover
+    ("3x3_stride2", Geom(2, 32, 32, 14, 14, 3, 3, 2, 2, 1, 1), 0.5, 0.5),
+    ("5x5_pad2", Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2), 0.5, 0.5),
+    ("r3_s1_stride_1x2", Geom(1, 32, 16, 8, 11, 3, 1, 2, 1, 1, 0), 0.5, 0.5),
+    ("1x1_stride2", Geom(1, 32, 32, 9, 9, 1, 1, 2, 2, 0, 0), 0.5, 0.5),
+]
+
+
+@pytest.mark.parametrize("label,g,px,pdy", SMALL, ids=[s[0] for s in SMALL])
+def test_small_shapes_all_passes(label, g, px, pdy):
+    x, w, dy = synth(g, px, pdy, seed=3)
+    check_all_passes_full(g, x, w, dy, label)
+
+
+@pytest.mark.parametrize("p", [0.0, 0.9, 1.0])
+def test_degenerate_sparsity(p):
+    """Fully dense, very sparse and all-zero tested operands."""
+    g = Geom(2, 32, 128, 11, 13, 3, 3, 1, 1, 1, 1)
+    x, w, dy = synth(g, min(p, 0.9), min(p, 0.9), seed=5)
+    if p == 1.0:
+        x[:] = 0.0
+        dy[:] = 0.0
+    check_all_passes_full(g, x, w, dy, f"p={p}")
+
+
+def test_zero_semantics_on_gpu():
+    """-0.0 is skipped like +0.0, denormals are not flushed before the test: a denormal input
+    times a huge filter value must survive in the sparse result as in the oracle."""
+    g = Geom(1, 16, 16, 8, 8, 3, 3, 1, 1, 1, 1)
+    x = np.zeros(g.x_shape, np.float32)
+    x[0, :, ::2, ::2] = -0.0
+    x[0, 3, 4, 4] = 1e-40            # denormal
+    x[0, 5, 1, 6] = 2.0
+    w = np.full(g.w_shape, 1e30, np.float32)
+    dy = np.zeros(g.y_shape, np.float32)
+    dy[0, 2, 3, 3] = -0.0
+    dy[0, 7, 5, 2] = 1e-40
+    check_all_passes_full(g, x, w, dy, "zero-semantics", passes=("fwd", "bwi"))
+    L = DeviceLayer(g, x, w, dy)
+    y = L.fwd(False)
+    assert y[0, 0, 4, 4] > 0                     # the denormal contributed
+
+
+def test_sparse_equals_dense_control_and_is_deterministic():
+    g = Geom(2, 64, 128, 16, 16, 3, 3, 1, 1, 1, 1)
+    x, w, dy = synth(g, 0.5, 0.5, seed=9)
+    L = DeviceLayer(g, x, w, dy)
+    for fn in (L.fwd, L.bwi, L.bww):
+        a, b = fn(False), fn(False)
+        assert np.array_equal(a, b), "two runs of the sparse kernel differ"
+        c = fn(True)
+        assert np.allclose(a, c, rtol=1e-3, atol=1e-4)
+
+
+def test_config3_resnet3_2_full():
+    """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
+    L = stgen.RESNET3_2
+    g = geom_of(L)
+    x, w, dy = stgen.make_layer_tensors(L, seed=0)
+    check_all_passes_full(g, x, w, dy, "config3")
+
+
+def test_config2_vgg3_2_sampled():
+    """The benchmark workload at full size (N=16, 256->256 @56x56), sampled outputs."""
+    L = stgen.VGG3_2_N16
+    g = geom_of(L)
+    x, w, dy = stgen.make_layer_tensors(L, seed=0)
+    assert abs(stgen.zero_fraction(x) - 0.6) < 0.002 and abs(stgen.zero_fraction(dy) - 0.5) < 0.002
+    check_all_passes_sampled(g, x, w, dy, "config2")
+
+
+@pytest.mark.parametrize("layer", stgen.BOTTLENECK, ids=[l.name for l in stgen.BOTTLENECK])
+def test_config4_bottleneck_sampled(layer):
+    g = geom_of(layer)
+    x, w, dy = stgen.make_layer_tensors(layer, seed=0)
+    check_all_passes_sampled(g, x, w, dy, "config4-" + layer.name, n_samples=2048, n_bww=256)
+
+
+VGG_SMALL = [l for l in stgen.vgg16_stack(0.5) if l.H <= 28]
+
+
+@pytest.mark.parametrize("layer", [l for l in VGG_SMALL if l.H == 14][:1] + [l for l in VGG_SMALL if l.H == 28][:2],
+                         ids=lambda l: l.name)
+def test_config5_vgg_late_layers(layer):
+    g = geom_of(layer)
+    x, w, dy = stgen.make_layer_tensors(layer, seed=1)
+    if layer.H == 14:
+        check_all_passes_full(g, x, w, dy, "config5-" + layer.name)
+    else:
+        check_all_passes_sampled(g, x, w, dy, "config5-" + layer.name, n_samples=2048, n_bww=256)
+
+
+@pytest.mark.parametrize("p", [0.0, 0.3, 0.7, 0.9])
+def test_config5_sweep_levels_on_vgg5(p):
+    layer = stgen.vgg16_stack(p, n=8)[-1]
+    g = geom_of(layer)
+    x, w, dy = stgen.make_layer_tensors(layer, seed=2)
+    check_all_passes_sampled(g, x, w, dy, f"vgg5_3 p={p}", n_samples=2048, n_bww=256)
