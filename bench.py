@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the zero-skipping convolution passes on one MI355X.
+
+A step is one pass of the whole hot path -- st_conv_fwd, st_conv_bwi, st_conv_bww -- over one
+batch of the VGG16 conv3_2-shaped layer (N=16, C=K=256, 56x56, 3x3, stride 1, pad 1) with
+synthetic inputs: x = ReLU-shifted Gaussian with 60 % zeros, dy = Bernoulli-masked Gaussian with
+50 % zeros, He-normal filters.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  value = effective (dense-equivalent) TFLOP/s of the step,
+3 * 2*N*K*C*OH*OW*R*S / step time.  Extra objects: per-pass timings of the sparse entry points and
+of the dense controls, the sparse-over-dense speedup at 0/30/50/70/90 % zeros, the roofline of the
+dominant kernel, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_VECTOR = 157.3      # TFLOP/s, published MI355X fp32 vector peak (needs packed fp32 math)
+PEAK_FP32_FMA = 78.6          # TFLOP/s, 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz: one v_fma_f32 per lane-clock
+PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
+
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured for the kernel in this tree.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the 0-90 %% zero-fraction sweep")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sweep-iters", type=int, default=5)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one MI355X per box); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1911_10175_amd as st
+    import stgen
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    st.load_library()
+
+    L = stgen.VGG3_2_N16
+    d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
+    F = d.flops
+    stream = torch.cuda.current_stream()
+
+    def upload(x, w, dy):
+        return (torch.from_numpy(st.pack_activations(x)).to(dev),
+                torch.from_numpy(st.pack_filters(w)).to(dev),
+                torch.from_numpy(st.pack_activations(dy)).to(dev))
+
+    x_h, w_h, dy_h = stgen.make_layer_tensors(L, seed=0)
+    px, pdy = stgen.zero_fraction(x_h), stgen.zero_fraction(dy_h)
+    xd, wd, dyd = upload(x_h, w_h, dy_h)
+    y = torch.empty((L.N, L.K // 16, L.OH, L.OW, 16), device=dev)
+    dx = torch.empty((L.N, L.C // 16, L.H, L.W, 16), device=dev)
+    dw = torch.empty((L.K // 16, L.C // 16, L.S, L.R, 16, 16), device=dev)
+
+    def ws_for(p, dense):
+        n = st.st_conv_workspace_bytes(d, p, dense)
+        return torch.empty(max(n, 4) // 4, dtype=torch.float32, device=dev) if n else None
+
+    ws = {(p, dn): ws_for(p, dn) for p in (0, 1, 2) for dn in (False, True)}
+
+    def run_pass(name, dense, xin=None, dyin=None):
+        xin = xd if xin is None else xin
+        dyin = dyd if dyin is None else dyin
+        if name == "fwd":
+            (st.st_conv_fwd_dense if dense else st.st_conv_fwd)(d, xin, wd, y, ws[0, dense], stream)
+        elif name == "bwi":
+            (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(d, dyin, wd, dx, ws[1, dense], stream)
+        else:
+            (st.st_conv_bww_dense if dense else st.st_conv_bww)(d, xin, dyin, dw, ws[2, dense], stream)
+
+    def step():
+        run_pass("fwd", False)
+        run_pass("bwi", False)
+        run_pass("bww", False)
+
+    # ---- the timed region: W warm-up steps, then exactly K steps ----
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = 3 * F / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-pass timing with events on the launch stream ----
+    def time_pass(name, dense, iters, xin=None, dyin=None, warm=2):
+        for _ in range(warm):
+            run_pass(name, dense, xin, dyin)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for a, b in evs:
+            a.record(stream)
+            run_pass(name, dense, xin, dyin)
+            b.record(stream)
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs)
+        return ts[len(ts) // 2], sum(ts) / len(ts)
+
+    tested_p = {"fwd": px, "bwi": pdy, "bww": px}
+    passes = {}
+    for name in ("fwd", "bwi", "bww"):
+        s_med, s_avg = time_pass(name, False, args.steps)
+        d_med, d_avg = time_pass(name, True, args.steps)
+        passes[name] = {
+            "sparse_ms": round(s_med, 4), "dense_ms": round(d_med, 4),
+            "sparse_avg_ms": round(s_avg, 4),
+            "speedup_vs_dense": round(d_med / s_med, 3),
+            "effective_tflops": round(F / (s_med * 1e-3) / 1e12, 2),
+            "executed_tflops": round(F * (1 - tested_p[name]) / (s_med * 1e-3) / 1e12, 2),
+            "dense_tflops": round(F / (d_med * 1e-3) / 1e12, 2),
+            "dense_frac_of_mfma_peak": round(F / (d_med * 1e-3) / 1e12 / PEAK_FP32_MFMA, 3),
+            "tested_zero_fraction": round(tested_p[name], 4),
+        }
+
+    # ---- roofline of the dominant kernel ----
+    # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy), so the
+    # event time of st_conv_fwd is that kernel's launch duration.  Algorithmic work per launch:
+    # F * (1 - realised zero fraction) flops on the vector ALUs.
+    dom = max(passes, key=lambda k: passes[k]["sparse_avg_ms"])
+    fwd_avg_ms = passes["fwd"]["sparse_avg_ms"]
+    achieved = F * (1 - px) / (fwd_avg_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "fwd_sparse_kernel<3,3,8,8,2> (st_conv_fwd; st_conv_bwi runs the same kernel)",
+        "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_FP32_VECTOR, 4),
+        "peak_unpacked_fma": PEAK_FP32_FMA, "frac_of_unpacked_fma_peak": round(achieved / PEAK_FP32_FMA, 4),
+        "avg_launch_ms": fwd_avg_ms, "algorithmic_flops_per_launch": F * (1 - px),
+        "traffic": MEASURED_TRAFFIC_BYTES, "slowest_pass": dom,
+    }
+
+    # ---- sparse-over-dense speedup at 0-90 % zeros ----
+    sweep = []
+    if not args.no_sweep:
+        for p in (0.0, 0.3, 0.5, 0.7, 0.9):
+            xs_h = stgen.relu_sparse((L.N, L.C, L.H, L.W), p, 100)
+            dys_h = stgen.bernoulli_masked((L.N, L.K, L.OH, L.OW), p, 102, 103)
+            xs = torch.from_numpy(st.pack_activations(xs_h)).to(dev)
+            dys = torch.from_numpy(st.pack_activations(dys_h)).to(dev)
+            row = {"zero_fraction": p}
+            for name in ("fwd", "bwi", "bww"):
+                s_med, _ = time_pass(name, False, args.sweep_iters, xs, dys, warm=1)
+                d_med, _ = time_pass(name, True, args.sweep_iters, xs, dys, warm=1)
+                row[name] = {"sparse_ms": round(s_med, 4), "dense_ms": round(d_med, 4),
+                             "speedup": round(d_med / s_med, 3),
+                             "effective_tflops": round(F / (s_med * 1e-3) / 1e12, 2)}
+            sweep.append(row)
+            del xs, dys
+
+    # ---- CPU oracle on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu:
+        from oracle import st_ref
+
+        def oracle_step(n_img):
+            g = st_ref.Geom(n_img, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
+            xs_, dys_ = x_h[:n_img], dy_h[:n_img]
+            t = time.perf_counter()
+            st_ref.conv_fwd(g, xs_, w_h)
+            st_ref.conv_bwi(g, dys_, w_h)
+            st_ref.conv_bww(g, xs_, dys_)
+            return time.perf_counter() - t, 3 * g.flops
+
+        t1img, f1 = oracle_step(1)
+        n_img = int(max(1, min(L.N, 15.0 // max(t1img, 1e-3))))
+        if n_img > 1:
+            tt, ff = oracle_step(n_img)
+        else:
+            tt, ff = t1img, f1
+        cpu = {"value": round(ff / tt / 1e12, 5), "unit": "TFLOP/s", "cores": st_ref.threads(), "kind": "oracle",
+               "sample": f"FWD+BWI+BWW of the first {n_img} of {L.N} images of the same tensors, "
+                         f"{tt:.2f} s of wall time; dense-equivalent flops / time"}
+
+    out = {
+        "metric": "effective conv TFLOP/s (FWD+BWI+BWW, zero-skipping entry points)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "vgg3_2-shaped 3x3 conv layer N=16 C=256 K=256 56x56 stride 1 pad 1; "
+                               "x ReLU-shifted Gaussian, dy Bernoulli-masked Gaussian, He-normal filters, seed 0",
+                   "zero_fraction_x": round(px, 4), "zero_fraction_dy": round(pdy, 4),
+                   "flops_per_pass": F},
+        "passes": passes,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "sweep": sweep,
+        "paper_context": "SparseTrain reports 2.19x/1.37x/1.31x/1.51x projected conv-training speedups for "
+                         "VGG16/ResNet-34/ResNet-50/Fixup ResNet-50 on a 6-core Skylake-X CPU (Table 5); "
+                         "other machine, not a target",
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
