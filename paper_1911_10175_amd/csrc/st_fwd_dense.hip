@@ -31,7 +31,7 @@ struct FwdDenseCfg {
 };
 
 template <int R, int S>
-__global__ __launch_bounds__(256) void fwd_dense_kernel(Geom g, const float *__restrict__ in,
+__global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *__restrict__ in,
                                                         const float *__restrict__ f,
                                                         float *__restrict__ out,
                                                         int tiles_w, int tiles_h, int ktiles, int total)

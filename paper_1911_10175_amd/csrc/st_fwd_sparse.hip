@@ -14,6 +14,7 @@
 //    over all of them, taken by the whole wavefront, so no lane ever idles on a zero.
 //  * Filters for the current input channel (R*S*KPL values per lane) sit in registers and are
 //    reused by every non-zero pixel of the tile; they stream from L2, 64 B per 16 lanes.
+#include <cstdlib>
 #include <type_traits>
 
 #include "st_common.hpp"
@@ -44,8 +45,8 @@ struct FwdSparseCfg {
     static constexpr int KT = 64 * KPL;                     // output channels per wavefront
 };
 
-template <int R, int S, int TH, int TW, int KPL>
-__global__ __launch_bounds__(256) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
+template <int R, int S, int TH, int TW, int KPL, int MINW>
+__global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
                                                          const float *__restrict__ f,
                                                          float *__restrict__ out,
                                                          int tiles_w, int tiles_h, int ktiles, int total)
@@ -85,6 +86,63 @@ __global__ __launch_bounds__(256) void fwd_sparse_kernel(Geom g, const float *__
         fp[j] = f + (size_t)kb * CiB * (S * R * kBlk * kBlk) + (k % kBlk);
     }
 
+    // filters of one input channel (flat index c = 16*cb + ci): R*S*KPL registers per lane
+    auto load_w = [&](int c, float (&wv)[KPL][S * R]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) {
+            const float *p = fp[j] + (size_t)(c / kBlk) * (S * R * kBlk * kBlk) + (c % kBlk) * kBlk;
+#pragma unroll
+            for (int tp = 0; tp < S * R; ++tp) wv[j][tp] = p[tp * (kBlk * kBlk)];
+        }
+    };
+
+    // all multiply-adds of one input channel of the staged block
+    auto process = [&](int ci, const float (&wv)[KPL][S * R]) __attribute__((always_inline)) {
+        // one channel of the halo, one pixel per lane
+        float xv[NXV];
+        unsigned m32[2 * NXV];
+#pragma unroll
+        for (int j = 0; j < NXV; ++j) {
+            const int pix = j * kWave + lane;
+            xv[j] = (pix < HP) ? lds[ci * PST + pix] : 0.f;
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(xv[j] != 0.f);
+            m32[2 * j] = (unsigned)m;
+            m32[2 * j + 1] = (unsigned)(m >> 32);
+        }
+        // one branch per halo pixel; all register indices below are compile-time constants
+        static_for<0, HP>([&](auto I) __attribute__((always_inline)) {
+            constexpr int i = decltype(I)::value;
+            constexpr int a = i / HW, b = i % HW;
+            if (m32[i / 32] & (1u << (i % 32))) {
+                const float xs = __int_as_float(
+                    __builtin_amdgcn_readlane(__float_as_int(xv[i / 64]), i % 64));
+#pragma unroll
+                for (int v = 0; v < S; ++v) {
+                    const int ol = a - v;
+                    if (ol < 0 || ol >= TH) continue;
+#pragma unroll
+                    for (int u = 0; u < R; ++u) {
+                        const int oc = b - u;
+                        if (oc < 0 || oc >= TW) continue;
+#pragma unroll
+                        for (int j = 0; j < KPL; ++j)
+                            acc[j][ol * TW + oc] = fmaf(xs, wv[j][v * R + u], acc[j][ol * TW + oc]);
+                    }
+                }
+            }
+        });
+    };
+
+    // Two filter register sets alternate: the loads for channel c+1 are in flight while the
+    // multiply-adds of channel c run, so the L2 latency of the filter stream is hidden.
+    float wA[KPL][S * R], wB[KPL][S * R];
+    load_w(0, wA);
+    // s_waitcnt vmcnt(NW) with the other counters left at their maxima: vector loads return in
+    // order, so this waits for everything older than the NW most recent loads (one filter set).
+    constexpr int NW = KPL * S * R;
+    static_assert(NW < 64, "vmcnt is a 6-bit counter");
+    constexpr int kWaitOlderSet = (NW & 0xF) | ((NW >> 4) << 14) | (0x7 << 4) | (0xF << 8);
+
     for (int cb = 0; cb < CiB; ++cb) {
         // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----
         __builtin_amdgcn_wave_barrier();
@@ -108,52 +166,14 @@ __global__ __launch_bounds__(256) void fwd_sparse_kernel(Geom g, const float *__
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        const float *fcb[KPL];
-#pragma unroll
-        for (int j = 0; j < KPL; ++j) fcb[j] = fp[j] + (size_t)cb * (S * R * kBlk * kBlk);
-
-        for (int ci = 0; ci < kBlk; ++ci) {
-            // one channel of the halo, one pixel per lane
-            float xv[NXV];
-            unsigned m32[2 * NXV];
-#pragma unroll
-            for (int j = 0; j < NXV; ++j) {
-                const int pix = j * kWave + lane;
-                xv[j] = (pix < HP) ? lds[ci * PST + pix] : 0.f;
-                const unsigned long long m = __builtin_amdgcn_ballot_w64(xv[j] != 0.f);
-                m32[2 * j] = (unsigned)m;
-                m32[2 * j + 1] = (unsigned)(m >> 32);
-            }
-            // filters of this input channel
-            float wv[KPL][S * R];
-#pragma unroll
-            for (int j = 0; j < KPL; ++j)
-#pragma unroll
-                for (int tp = 0; tp < S * R; ++tp)
-                    wv[j][tp] = fcb[j][tp * (kBlk * kBlk) + ci * kBlk];
-
-            // one branch per halo pixel; all register indices below are compile-time constants
-            static_for<0, HP>([&](auto I) __attribute__((always_inline)) {
-                constexpr int i = decltype(I)::value;
-                constexpr int a = i / HW, b = i % HW;
-                if (m32[i / 32] & (1u << (i % 32))) {
-                    const float xs = __int_as_float(
-                        __builtin_amdgcn_readlane(__float_as_int(xv[i / 64]), i % 64));
-#pragma unroll
-                    for (int v = 0; v < S; ++v) {
-                        const int ol = a - v;
-                        if (ol < 0 || ol >= TH) continue;
-#pragma unroll
-                        for (int u = 0; u < R; ++u) {
-                            const int oc = b - u;
-                            if (oc < 0 || oc >= TW) continue;
-#pragma unroll
-                            for (int j = 0; j < KPL; ++j)
-                                acc[j][ol * TW + oc] = fmaf(xs, wv[j][v * R + u], acc[j][ol * TW + oc]);
-                        }
-                    }
-                }
-            });
+        for (int ci = 0; ci < kBlk; ci += 2) {
+            const int c = cb * kBlk + ci;
+            load_w(c + 1, wB);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);     // wA has arrived; wB stays in flight
+            process(ci, wA);
+            load_w(min(c + 2, g.Ci - 1), wA);
+            __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+            process(ci + 1, wB);
         }
     }
 
@@ -177,7 +197,7 @@ __global__ __launch_bounds__(256) void fwd_sparse_kernel(Geom g, const float *__
     }
 }
 
-template <int R, int S, int TH, int TW, int KPL>
+template <int R, int S, int TH, int TW, int KPL, int MINW>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
@@ -186,7 +206,7 @@ hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out
     const long long total = (long long)tiles_w * tiles_h * ktiles * g.N;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)((total + Cfg::WAVES - 1) / Cfg::WAVES));
-    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL>), grid, dim3(256), 0, s, g, in, f, out,
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW>), grid, dim3(256), 0, s, g, in, f, out,
                        tiles_w, tiles_h, ktiles, (int)total);
     return hipGetLastError();
 }
@@ -203,13 +223,25 @@ bool fwd_sparse_supported(const Geom &g)
 
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
+    // ST_FWD_SPARSE_CFG selects a tile configuration by hand (tuning aid); unset = heuristic.
+    const char *env = getenv("ST_FWD_SPARSE_CFG");
+    const int cfg = env ? atoi(env) : 0;
     if (g.R == 3 && g.S == 3) {
-        if (g.Ko % 128 == 0) return launch_cfg<3, 3, 8, 8, 2>(g, in, f, out, s);
-        return launch_cfg<3, 3, 8, 8, 1>(g, in, f, out, s);
+        const bool wide = g.Ko % 128 == 0;
+        switch (cfg) {
+        case 1: return launch_cfg<3, 3, 8, 8, 1, 3>(g, in, f, out, s);
+        case 2: if (wide) return launch_cfg<3, 3, 4, 8, 2, 4>(g, in, f, out, s); break;
+        case 3: return launch_cfg<3, 3, 4, 8, 1, 4>(g, in, f, out, s);
+        case 4: return launch_cfg<3, 3, 8, 8, 1, 4>(g, in, f, out, s);
+        case 5: if (wide) return launch_cfg<3, 3, 4, 8, 2, 3>(g, in, f, out, s); break;
+        default: break;
+        }
+        if (wide) return launch_cfg<3, 3, 8, 8, 2, 2>(g, in, f, out, s);
+        return launch_cfg<3, 3, 8, 8, 1, 3>(g, in, f, out, s);
     }
     if (g.R == 1 && g.S == 1) {
-        if (g.Ko % 128 == 0) return launch_cfg<1, 1, 8, 8, 2>(g, in, f, out, s);
-        return launch_cfg<1, 1, 8, 8, 1>(g, in, f, out, s);
+        if (g.Ko % 128 == 0) return launch_cfg<1, 1, 8, 8, 2, 2>(g, in, f, out, s);
+        return launch_cfg<1, 1, 8, 8, 1, 4>(g, in, f, out, s);
     }
     return hipErrorInvalidValue;
 }
