@@ -40,7 +40,7 @@ template <int R, int S, int TH, int TW, int KPL>
 struct FwdSparseCfg {
     static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
     static constexpr int NXV = (HP + 63) / 64;              // registers holding one channel of the halo
-    static constexpr int PST = ((HP + 7) / 8) * 8 + 4;      // LDS pixel stride, = 4 (mod 8)
+    static constexpr int PST = ((HP + 7) / 8) * 8 + 4;      // LDS pixel stride, = 4 (mod 8), >= HP rounded up to 4
     static constexpr int WAVES = 4;
     static constexpr int KT = 64 * KPL;                     // output channels per wavefront
 };
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
-    __shared__ float lds_all[Cfg::WAVES][kBlk * PST];
+    __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][kBlk * PST];
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int wid = blockIdx.x * Cfg::WAVES + wave;
@@ -98,38 +98,61 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 
     // all multiply-adds of one input channel of the staged block
     auto process = [&](int ci, const float (&wv)[KPL][S * R]) __attribute__((always_inline)) {
-        // one channel of the halo, one pixel per lane
-        float xv[NXV];
+        // Non-zero mask of this channel's halo: one pixel per lane, one compare, one ballot.
         unsigned m32[2 * NXV];
 #pragma unroll
         for (int j = 0; j < NXV; ++j) {
             const int pix = j * kWave + lane;
-            xv[j] = (pix < HP) ? lds[ci * PST + pix] : 0.f;
-            const unsigned long long m = __builtin_amdgcn_ballot_w64(xv[j] != 0.f);
+            const float xv = (pix < HP) ? lds[ci * PST + pix] : 0.f;
+            const unsigned long long m = __builtin_amdgcn_ballot_w64(xv != 0.f);
             m32[2 * j] = (unsigned)m;
             m32[2 * j + 1] = (unsigned)(m >> 32);
         }
-        // one branch per halo pixel; all register indices below are compile-time constants
-        static_for<0, HP>([&](auto I) __attribute__((always_inline)) {
-            constexpr int i = decltype(I)::value;
-            constexpr int a = i / HW, b = i % HW;
-            if (m32[i / 32] & (1u << (i % 32))) {
-                const float xs = __int_as_float(
-                    __builtin_amdgcn_readlane(__float_as_int(xv[i / 64]), i % 64));
+        // The values themselves are read four pixels at a time with one LDS read whose address is
+        // the same in every lane (a broadcast): each lane then holds the four inputs in registers
+        // and the multiply-adds need no cross-lane move.  The next group is in flight while the
+        // current one is processed; LDS reads return in order, so lgkmcnt(1) means "all but the
+        // newest read have arrived".
+        const float4 *lds4 = reinterpret_cast<const float4 *>(lds + ci * PST);
+        constexpr int NG = (HP + 3) / 4;
+        float4 cur = lds4[0];
+        static_for<0, NG>([&](auto G) __attribute__((always_inline)) {
+            constexpr int gidx = decltype(G)::value;
+            float4 nxt = cur;
+            if constexpr (gidx + 1 < NG) {
+                nxt = lds4[gidx + 1];
+                __builtin_amdgcn_s_waitcnt(0xC17F);      // lgkmcnt(1)
+            } else {
+                __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
+            }
+            const float xg[4] = {cur.x, cur.y, cur.z, cur.w};
+            // a group whose four pixels are all zero costs one test instead of four
+            constexpr unsigned gmask = 0xFu << ((gidx * 4) % 32);
+            if (m32[(gidx * 4) / 32] & gmask)
+            // one branch per halo pixel; all register indices below are compile-time constants
+            static_for<0, 4>([&](auto J) __attribute__((always_inline)) {
+                constexpr int i = gidx * 4 + decltype(J)::value;
+                if constexpr (i < HP) {
+                    constexpr int a = i / HW, b = i % HW;
+                    if (m32[i / 32] & (1u << (i % 32))) {
+                        const float xs = xg[i % 4];
 #pragma unroll
-                for (int v = 0; v < S; ++v) {
-                    const int ol = a - v;
-                    if (ol < 0 || ol >= TH) continue;
+                        for (int v = 0; v < S; ++v) {
+                            const int ol = a - v;
+                            if (ol < 0 || ol >= TH) continue;
 #pragma unroll
-                    for (int u = 0; u < R; ++u) {
-                        const int oc = b - u;
-                        if (oc < 0 || oc >= TW) continue;
+                            for (int u = 0; u < R; ++u) {
+                                const int oc = b - u;
+                                if (oc < 0 || oc >= TW) continue;
 #pragma unroll
-                        for (int j = 0; j < KPL; ++j)
-                            acc[j][ol * TW + oc] = fmaf(xs, wv[j][v * R + u], acc[j][ol * TW + oc]);
+                                for (int j = 0; j < KPL; ++j)
+                                    acc[j][ol * TW + oc] = fmaf(xs, wv[j][v * R + u], acc[j][ol * TW + oc]);
+                            }
+                        }
                     }
                 }
-            }
+            });
+            cur = nxt;
         });
     };
 
@@ -236,8 +259,9 @@ hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, flo
         case 5: if (wide) return launch_cfg<3, 3, 4, 8, 2, 3>(g, in, f, out, s); break;
         default: break;
         }
-        if (wide) return launch_cfg<3, 3, 8, 8, 2, 2>(g, in, f, out, s);
-        return launch_cfg<3, 3, 8, 8, 1, 3>(g, in, f, out, s);
+        if (cfg == 6 && wide) return launch_cfg<3, 3, 8, 8, 2, 2>(g, in, f, out, s);
+        if (wide) return launch_cfg<3, 3, 4, 8, 2, 4>(g, in, f, out, s);
+        return launch_cfg<3, 3, 4, 8, 1, 4>(g, in, f, out, s);
     }
     if (g.R == 1 && g.S == 1) {
         if (g.Ko % 128 == 0) return launch_cfg<1, 1, 8, 8, 2, 2>(g, in, f, out, s);
