@@ -3,21 +3,26 @@
 // Mapping of SparseTrain Sec. 3.4 (Alg. 4-5) onto a CDNA wavefront:
 //  * The filter-gradient accumulators are stationary (Sec. 3.4: T gradient vectors stay in
 //    registers for the whole sweep): a wavefront owns 64 output channels (one per lane) times
-//    16 input channels times R*S taps = 144 registers per lane for a 3x3 filter.
-//  * The tested operand is the input x.  One pixel's 16-channel block is 64 contiguous bytes in
-//    the blocked layout, fetched with one scalar load, so each channel value sits in a scalar
-//    register: the zero test is a scalar compare, the skip a scalar branch over R*S multiply-
-//    adds, and the non-zero value is the scalar operand of those multiply-adds (the broadcast
-//    of Alg. 5).  The paper vectorises this test along the minibatch because its vector
-//    register holds 16 values of one operand; a wavefront has separate scalar registers, so the
-//    test runs along the channel block and the layout needs no minibatch transposition.
+//    8 input channels times R*S taps = 72 registers per lane for a 3x3 filter, which leaves room
+//    for 4 wavefronts per SIMD; the scalar work of the zero tests of one wavefront then overlaps
+//    the vector work of the others.
+//  * The tested operand is the input x.  The tile of x for 64 input channels is staged in LDS by
+//    the workgroup (8 wavefronts = 4 channel blocks x 2 halves).  For four pixels at a time one
+//    LDS read with a lane per (pixel, channel) followed by one compare and a ballot gives the
+//    non-zero mask (the vector compare of Alg. 5, along channels and pixels instead of along the
+//    minibatch: the accumulators do not depend on the pixel, so no minibatch transposition of
+//    the layout is needed).  Each set bit costs one scalar bit test and branch; the value itself
+//    reaches all lanes through a same-address (broadcast) LDS read of the pixel's 8 channels.
 //  * The other operand, dy at the R*S neighbouring output pixels, is a vector over the lane's
-//    output channel read from an LDS tile that the 4 wavefronts of a workgroup (4 different
-//    16-channel input blocks) share.
+//    output channel read from the LDS halo tile; the 3x6 window of four adjacent pixels is read
+//    once per group.
 //  * The sum over the minibatch and the image is split over workgroups; each writes a partial
 //    gradient to the workspace and a second kernel adds the partials in a fixed order
 //    (Sec. 3.4, accumulation of partial results at the end of a sweep), so results are
 //    deterministic without floating-point atomics.
+#include <cstdlib>
+#include <type_traits>
+
 #include "st_common.hpp"
 
 namespace st {
@@ -28,41 +33,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
 {
     return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
-}
-
-// x != 0 for a wavefront-uniform value, decided on the scalar unit: clearing the sign bit leaves
-// zero exactly for +0 and -0 (denormals and NaNs count as non-zero).  The asm keeps the compiler
-// from turning the integer test back into a vector float compare.
-__device__ __forceinline__ bool scalar_nonzero(float v)
-{
-    unsigned mag;
-    asm volatile("s_and_b32 %0, %1, 0x7fffffff" : "=s"(mag) : "s"(__float_as_uint(v)) : "scc");
-    return mag != 0u;
-}
-
-// 16 channels of input pixel q of the tile (clamped into the image), wavefront-uniform address
-__device__ __forceinline__ void load_x16(const float *__restrict__ x, int n, int cb, int ih0, int iw0,
-                                         int q, int TW, int CB, int H, int W, float (&dst)[kBlk])
-{
-    const int ih = min(ih0 + q / TW, H - 1), iw = min(iw0 + q % TW, W - 1);
-    const float4 *p = reinterpret_cast<const float4 *>(x + act_off(n, cb, ih, iw, CB, H, W));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float4 v = p[j];
-        dst[4 * j + 0] = v.x; dst[4 * j + 1] = v.y; dst[4 * j + 2] = v.z; dst[4 * j + 3] = v.w;
-    }
-}
-
-// dy at the R*S output pixels that read input pixel q of the tile, for this lane's channel
-template <int R, int S, int HW>
-__device__ __forceinline__ void load_dy_taps(const float *dyT, int q, int TW, int lane, float (&dst)[S * R])
-{
-    const int a = q / TW, b = q % TW;
-#pragma unroll
-    for (int v = 0; v < S; ++v)
-#pragma unroll
-        for (int u = 0; u < R; ++u)
-            dst[v * R + u] = dyT[((a + S - 1 - v) * HW + (b + R - 1 - u)) * 64 + lane];
 }
 
 struct BwwArgs {
@@ -79,34 +49,53 @@ struct BwwCfg {
 };
 
 // ------------------------------------------------------------------------------------------
-// zero-skipping kernel: tiles run over the INPUT image; LDS holds the dy halo of the tile
+// zero-skipping kernel: tiles run over the INPUT image; LDS holds the x tile (64 channels) and
+// the dy halo of the tile (64 output channels)
 // ------------------------------------------------------------------------------------------
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 template <int R, int S, int TH, int TW>
-__global__ __launch_bounds__(256) void bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
-                                                         const float *__restrict__ dy,
-                                                         float *__restrict__ part)
+__global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
+                                                            const float *__restrict__ dy,
+                                                            float *__restrict__ part)
 {
     using Cfg = BwwCfg<R, S, TH, TW>;
-    constexpr int HW = Cfg::HW, HP = Cfg::HP;
+    constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
+    constexpr int CH = 8;                 // input channels per wavefront
+    constexpr int GP = 4;                 // pixels per group
+    static_assert(TW % GP == 0, "groups must not straddle rows");
+    constexpr int WC = GP + R - 1;        // dy window columns of a group
     __shared__ __attribute__((aligned(16))) float dyT[HP * 64];
+    __shared__ __attribute__((aligned(16))) float xT[TP * 64];
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
     const int split = blockIdx.x;
     const int kt = blockIdx.y / A.cgroups, cg = blockIdx.y % A.cgroups;
     const int CB = A.C / kBlk, KB = A.K / kBlk;
-    const int cb = cg * 4 + wave;
+    const int cbl = wave >> 1, h = wave & 1;          // channel block within the group of 64, half
+    const int cb = cg * 4 + cbl;
     const bool wave_active = cb < CB;
     const int k = kt * 64 + lane;
 
-    float acc[kBlk][S * R];
+    float acc[CH][S * R];
 #pragma unroll
-    for (int ci = 0; ci < kBlk; ++ci)
+    for (int ci = 0; ci < CH; ++ci)
 #pragma unroll
         for (int t = 0; t < S * R; ++t) acc[ci][t] = 0.f;
 
     const int u0 = (int)((long long)A.units * split / A.splits);
     const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
+
+    // lane -> (pixel of the group, channel of the block) for the mask read
+    const int mpix = lane >> 4, mch = lane & 15;
 
     for (int unit = u0; unit < u1; ++unit) {
         int t = unit;
@@ -117,8 +106,9 @@ __global__ __launch_bounds__(256) void bww_sparse_kernel(BwwArgs A, const float 
         const int ohs = ih0 + A.ph - (S - 1), ows = iw0 + A.pw - (R - 1);
 
         __syncthreads();
-        // stage dy[n, kt*64 .. +63, halo] as [pixel][64 k]; 16 float4 per pixel
-        for (int idx = threadIdx.x; idx < HP * 16; idx += 256) {
+        // dy[n, kt*64 .. +63, halo] as [pixel][64 k]; x[n, cg*64 .. +63, tile] as [pixel][64 c];
+        // 16 float4 per pixel, zeros outside the image and beyond the channel count
+        for (int idx = threadIdx.x; idx < HP * 16; idx += 512) {
             const int pix = idx >> 4, q = idx & 15;
             const int oh = ohs + pix / HW, ow = ows + pix % HW;
             const int kb = kt * 4 + (q >> 2);
@@ -127,50 +117,74 @@ __global__ __launch_bounds__(256) void bww_sparse_kernel(BwwArgs A, const float 
                 val = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
             *reinterpret_cast<float4 *>(dyT + pix * 64 + q * 4) = val;
         }
+        for (int idx = threadIdx.x; idx < TP * 16; idx += 512) {
+            const int pix = idx >> 4, q = idx & 15;
+            const int ih = ih0 + pix / TW, iw = iw0 + pix % TW;
+            const int cbq = cg * 4 + (q >> 2);
+            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ih < A.H && iw < A.W && cbq < CB)
+                val = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
+            *reinterpret_cast<float4 *>(xT + pix * 64 + q * 4) = val;
+        }
         __syncthreads();
         if (!wave_active) continue;
 
-        // Software pipeline over the pixels of the tile: the scalar load of the next pixel's 16
-        // channels and the LDS reads of its dy neighbourhood are issued before the multiply-adds
-        // of the current pixel.  Coordinates are clamped for the loads (always in bounds); pixels
-        // outside the image are skipped by the validity test.
-        float xs[kBlk], dyv[S * R];
-        load_x16(x, n, cb, ih0, iw0, 0, TW, CB, A.H, A.W, xs);
-        load_dy_taps<R, S, HW>(dyT, 0, TW, lane, dyv);
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        for (int q = 0; q < TH * TW; ++q) {
-            float xn[kBlk], dyn[S * R];
-            const int qn = (q + 1 < TH * TW) ? q + 1 : q;
-            load_x16(x, n, cb, ih0, iw0, qn, TW, CB, A.H, A.W, xn);
-            load_dy_taps<R, S, HW>(dyT, qn, TW, lane, dyn);
-            const bool valid = (ih0 + q / TW < A.H) && (iw0 + q % TW < A.W);
-            if (valid) {
+        for (int g0 = 0; g0 < TP; g0 += GP) {                // groups of GP pixels along a row
+            const int a = g0 / TW, b0 = g0 % TW;
+            // non-zero mask of the group: bit 16*j + c for pixel j, channel c of the block
+            const float mval = xT[(g0 + mpix) * 64 + cbl * 16 + mch];
+            const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
+            const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
+            if ((mlo | mhi) == 0u) continue;                 // nothing to do for these 4 pixels x 16 channels
+            // dy window: rows a .. a+S-1, columns b0 .. b0+WC-1 of the halo, this lane's channel
+            float dyw[S][WC];
 #pragma unroll
-                for (int ci = 0; ci < kBlk; ++ci) {
-                    if (scalar_nonzero(xs[ci])) {
+            for (int r = 0; r < S; ++r)
 #pragma unroll
-                        for (int tp = 0; tp < S * R; ++tp) acc[ci][tp] = fmaf(xs[ci], dyv[tp], acc[ci][tp]);
-                    }
+                for (int cc = 0; cc < WC; ++cc) dyw[r][cc] = dyT[((a + r) * HW + b0 + cc) * 64 + lane];
+            // x of pixel 0 of the group: 8 channels, same address in all lanes
+            const float4 *xq = reinterpret_cast<const float4 *>(xT + g0 * 64 + cbl * 16 + h * CH);
+            float4 xlo = xq[0], xhi = xq[1];
+            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): window and first pixel are here
+            static_for<0, GP>([&](auto J) __attribute__((always_inline)) {
+                constexpr int j = decltype(J)::value;
+                float4 nlo = xlo, nhi = xhi;
+                if constexpr (j + 1 < GP) {                  // next pixel's values fly during this pixel's work
+                    nlo = xq[(j + 1) * 16];
+                    nhi = xq[(j + 1) * 16 + 1];
                 }
-            }
-            // the prefetched operands have had the whole pixel's arithmetic to arrive; waiting
-            // here (lgkmcnt(0)) keeps the compiler from waiting for them before that arithmetic
-            __builtin_amdgcn_s_waitcnt(0xC07F);
+                const float xs[CH] = {xlo.x, xlo.y, xlo.z, xlo.w, xhi.x, xhi.y, xhi.z, xhi.w};
+                const unsigned mw = (j < 2) ? mlo : mhi;
+                constexpr int sh = (j % 2) * 16;
+                const unsigned bits = (mw >> sh) >> (h * CH) & 0xFFu;     // this wave's 8 channels
+                if (bits) {
+                    static_for<0, CH>([&](auto CI) __attribute__((always_inline)) {
+                        constexpr int ci = decltype(CI)::value;
+                        if (bits & (1u << ci)) {
 #pragma unroll
-            for (int ci = 0; ci < kBlk; ++ci) xs[ci] = xn[ci];
+                            for (int v = 0; v < S; ++v)
 #pragma unroll
-            for (int tp = 0; tp < S * R; ++tp) dyv[tp] = dyn[tp];
+                                for (int u = 0; u < R; ++u)
+                                    acc[ci][v * R + u] =
+                                        fmaf(xs[ci], dyw[S - 1 - v][j + R - 1 - u], acc[ci][v * R + u]);
+                        }
+                    });
+                }
+                if constexpr (j + 1 < GP) __builtin_amdgcn_s_waitcnt(0xC07F);
+                xlo = nlo;
+                xhi = nhi;
+            });
         }
     }
 
     if (wave_active && k < A.K) {
         const int kb = k / kBlk, ki = k % kBlk;
         float *p = part + (size_t)split * A.K * A.C * (S * R) +
-                   ((size_t)kb * CB + cb) * (S * R * kBlk * kBlk) + ki;
+                   ((size_t)kb * CB + cb) * (S * R * kBlk * kBlk) + (h * CH) * kBlk + ki;
 #pragma unroll
         for (int tp = 0; tp < S * R; ++tp)
 #pragma unroll
-            for (int ci = 0; ci < kBlk; ++ci) p[tp * (kBlk * kBlk) + ci * kBlk] = acc[ci][tp];
+            for (int ci = 0; ci < CH; ++ci) p[tp * (kBlk * kBlk) + ci * kBlk] = acc[ci][tp];
     }
 }
 
@@ -279,7 +293,7 @@ __global__ __launch_bounds__(256) void bww_reduce_kernel(const float4 *__restric
     dw[i] = s;
 }
 
-constexpr int kSparseTH = 8, kSparseTW = 16;
+constexpr int kSparseTH = 8, kSparseTW = 8;
 constexpr int kDenseTH = 8, kDenseTW = 16;
 
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
@@ -295,7 +309,11 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
     A.units = d.N * A.tiles_h * A.tiles_w;
     A.cgroups = ceil_div(d.C, 64);
     const int groups = ceil_div(d.K, 64) * A.cgroups;
-    int splits = ceil_div(1024, groups);         // aim at >= 4 workgroups per compute unit
+    // number of partial sums: enough workgroups to fill the chip (256 compute units, 2 resident
+    // workgroups each); ST_BWW_WGS overrides the target (tuning aid)
+    const char *env = getenv("ST_BWW_WGS");
+    const int target = env ? atoi(env) : 512;
+    int splits = ceil_div(target > 0 ? target : 512, groups);
     if (splits > A.units) splits = A.units;
     if (splits < 1) splits = 1;
     A.splits = splits;
@@ -346,9 +364,9 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
     if (d.R == 3)
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(256), 0, s, A, x, dy, part);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
     else
-        hipLaunchKernelGGL((bww_sparse_kernel<1, 1, kSparseTH, kSparseTW>), grid, dim3(256), 0, s, A, x, dy, part);
+        hipLaunchKernelGGL((bww_sparse_kernel<1, 1, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
