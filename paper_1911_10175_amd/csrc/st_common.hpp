@@ -44,7 +44,11 @@ hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float
 bool fwd_sparse_supported(const Geom &g);
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s);
 bool fwd_dense_supported(const Geom &g);
-hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *f, float *out, hipStream_t s);
+// the dense kernel reads filters from a reformatted copy (fwd_dense_filter_bytes) written by
+// launch_reformat_filters; transpose selects the BWI form (channel roles swapped, taps reversed)
+size_t fwd_dense_filter_bytes(const Geom &g);
+hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w, float *wd, hipStream_t s);
+hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s);
 
 bool bww_fast_supported(const st_conv_desc &d);
 size_t bww_sparse_workspace(const st_conv_desc &d);

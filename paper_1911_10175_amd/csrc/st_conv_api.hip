@@ -68,13 +68,15 @@ st_status dev(hipError_t e) { return e == hipSuccess ? ST_OK : ST_ERR_DEVICE; }
 size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dense)
 {
     switch (pass) {
-    case ST_PASS_FWD:
-        return 0;
+    case ST_PASS_FWD: {
+        const Geom g = fwd_geom(d, o);
+        return dense && st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
+    }
     case ST_PASS_BWI: {
         Geom g;
         if (!bwi_as_fwd(d, o, &g)) return 0;
-        const bool fast = dense ? st::fwd_dense_supported(g) : st::fwd_sparse_supported(g);
-        return fast ? filter_bytes(d) : 0;
+        if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
+        return st::fwd_sparse_supported(g) ? filter_bytes(d) : 0;
     }
     case ST_PASS_BWW:
         if (!st::bww_fast_supported(d)) return 0;
@@ -87,7 +89,6 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
 st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *y, void *ws,
                   size_t ws_bytes, void *stream, bool dense)
 {
-    (void)ws; (void)ws_bytes;
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
@@ -95,8 +96,11 @@ st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geom g = fwd_geom(*d, o);
     if (dense) {
-        if (st::fwd_dense_supported(g)) return dev(st::launch_fwd_dense(g, x, w, y, s));
-        return dev(st::launch_generic_fwd(*d, x, w, y, false, s));
+        if (!st::fwd_dense_supported(g)) return dev(st::launch_generic_fwd(*d, x, w, y, false, s));
+        if (!ws_ok(ws, ws_bytes, st::fwd_dense_filter_bytes(g))) return ST_ERR_WORKSPACE;
+        float *wd = static_cast<float *>(ws);
+        if (st::launch_reformat_filters(g, false, w, wd, s) != hipSuccess) return ST_ERR_DEVICE;
+        return dev(st::launch_fwd_dense(g, x, wd, y, s));
     }
     if (st::fwd_sparse_supported(g)) return dev(st::launch_fwd_sparse(g, x, w, y, s));
     return dev(st::launch_generic_fwd(*d, x, w, y, true, s));
@@ -114,11 +118,15 @@ st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float 
     const bool fast = bwi_as_fwd(*d, o, &g) &&
                       (dense ? st::fwd_dense_supported(g) : st::fwd_sparse_supported(g));
     if (!fast) return dev(st::launch_generic_bwi(*d, dy, w, dx, !dense, s));
-    if (!ws_ok(ws, ws_bytes, filter_bytes(*d))) return ST_ERR_WORKSPACE;
     float *wt = static_cast<float *>(ws);
-    hipError_t e = st::launch_transpose_filters(*d, w, wt, s);
-    if (e != hipSuccess) return ST_ERR_DEVICE;
-    return dev(dense ? st::launch_fwd_dense(g, dy, wt, dx, s) : st::launch_fwd_sparse(g, dy, wt, dx, s));
+    if (dense) {
+        if (!ws_ok(ws, ws_bytes, st::fwd_dense_filter_bytes(g))) return ST_ERR_WORKSPACE;
+        if (st::launch_reformat_filters(g, true, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
+        return dev(st::launch_fwd_dense(g, dy, wt, dx, s));
+    }
+    if (!ws_ok(ws, ws_bytes, filter_bytes(*d))) return ST_ERR_WORKSPACE;
+    if (st::launch_transpose_filters(*d, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
+    return dev(st::launch_fwd_sparse(g, dy, wt, dx, s));
 }
 
 st_status run_bww(const st_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,

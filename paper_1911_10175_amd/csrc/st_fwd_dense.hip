@@ -4,11 +4,19 @@
 //
 // Implicit GEMM with v_mfma_f32_32x32x2_f32: rows = 32 output pixels, columns = 32 output
 // channels, reduction = 2 input channels of one filter tap per instruction.  A wavefront owns an
-// 8x8 pixel tile times 64 output channels (2x2 MFMA blocks, 64 accumulator registers).  The
-// input halo of the tile for one 16-channel block is staged in a wavefront-private LDS region
-// (zero padding is applied there once); for every tap the A operand is read from LDS at the
-// shifted pixel, the B operand (filters) comes straight from global memory / L2 in the
-// library's [K/16][C/16][S][R][16][16] layout.  No tests, no skipping.
+// 8x8 pixel tile times 32 output channels (two accumulator blocks).  The 4 wavefronts of a
+// workgroup cover KQ column blocks of 4/KQ pixel tiles; the wavefronts that share a pixel tile
+// stage its input halo for one 16-channel block cooperatively in LDS (zero padding is applied
+// there once), double-buffered: the global loads for block cb+1 are issued at the first tap of
+// block cb and written to the other buffer after the last tap, one barrier per block.  For every
+// tap the A operand is read from LDS at the shifted pixel.  The B operand (filters) is read from
+// a copy that a small prologue kernel writes into the workspace in the order the MFMA lanes
+// consume it, [K/32][C/16][tap][c half][32 k][8 c]: a lane fetches its 8 values of a step with
+// two 16-byte loads and a wavefront reads 2 KB contiguously (fetching them element-wise from the
+// library layout takes 8 load instructions per 16 MFMAs and holds the matrix pipe at about half
+// rate); the loads for step s+1 are in flight during the MFMAs of step s.  No tests, no skipping.
+#include <cstdlib>
+
 #include "st_common.hpp"
 
 namespace st {
@@ -25,55 +33,56 @@ template <int R, int S>
 struct FwdDenseCfg {
     static constexpr int TH = 8, TW = 8;
     static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
-    static constexpr int XST = 20;          // floats per staged pixel (16 channels + 4 pad)
-    static constexpr int WAVES = 4;
-    static constexpr int KT = 64;
+    static constexpr int XST = 20;                  // floats per staged pixel (16 channels + 4 pad)
+    static constexpr int BUF = ((HP * XST + 63) / 64) * 64;   // floats per halo buffer
 };
 
-template <int R, int S>
+// KQ = column blocks (of 32 output channels) per workgroup: 1, 2 or 4; TQ = 4/KQ pixel tiles.
+template <int R, int S, int KQ>
 __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *__restrict__ in,
-                                                        const float *__restrict__ f,
-                                                        float *__restrict__ out,
-                                                        int tiles_w, int tiles_h, int ktiles, int total)
+                                                           const float *__restrict__ wd,
+                                                           float *__restrict__ out, int tiles_w,
+                                                           int tiles_h, int kgroups, int total_tiles)
 {
     using Cfg = FwdDenseCfg<R, S>;
-    constexpr int TH = Cfg::TH, TW = Cfg::TW, HW = Cfg::HW, HP = Cfg::HP, XST = Cfg::XST;
-    __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][HP * XST];
+    constexpr int TH = Cfg::TH, TW = Cfg::TW, HW = Cfg::HW, HP = Cfg::HP, XST = Cfg::XST, BUF = Cfg::BUF;
+    constexpr int TAPS = S * R, TQ = 4 / KQ;
+    constexpr int NLD = (HP * 4 + KQ * 64 - 1) / (KQ * 64);      // float4 loads per lane and block
+    __shared__ __attribute__((aligned(16))) float lds_all[2][TQ][BUF];
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int wid = blockIdx.x * Cfg::WAVES + wave;
-    if (wid >= total) return;                       // no block-level barrier is used below
-    float *lds = lds_all[wave];
-
-    int t = wid;
-    const int kt = t % ktiles; t /= ktiles;
+    const int kqi = wave % KQ, tqi = wave / KQ;
+    const int kg = blockIdx.x % kgroups, tg = blockIdx.x / kgroups;
+    const int tile = tg * TQ + tqi;
+    const bool tile_ok = tile < total_tiles;
+    int t = tile_ok ? tile : 0;
     const int tw = t % tiles_w; t /= tiles_w;
     const int th = t % tiles_h;
     const int n = t / tiles_h;
     const int oh0 = th * TH, ow0 = tw * TW;
     const int ih0 = oh0 - g.ph, iw0 = ow0 - g.pw;
     const int CiB = g.Ci / kBlk, KoB = g.Ko / kBlk;
+    const int kb32 = kg * KQ + kqi;                 // this wavefront's column block
+    const bool k_ok = kb32 * 32 < g.Ko;
+    const bool active = tile_ok && k_ok;
 
     const int l32 = lane % 32, half = lane / 32;
 
-    floatx16 acc[2][2];
+    floatx16 acc[2];
 #pragma unroll
     for (int pb = 0; pb < 2; ++pb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[pb][kb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[pb][r] = 0.f;
 
-    // B operand: lane supplies filter element (k = kt*64 + kb2*32 + l32, c = j + 8*half), j = 0..7
-    const float *fp[2];
-    bool kact[2];
-#pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2) {
-        const int k = kt * Cfg::KT + kb2 * 32 + l32;
-        kact[kb2] = k < g.Ko;
-        const int kb = kact[kb2] ? k / kBlk : 0;
-        fp[kb2] = f + (size_t)kb * CiB * (S * R * kBlk * kBlk) + (half * 8) * kBlk + (k % kBlk);
-    }
+    // B operand: lane supplies filter element (k = kb32*32 + l32, c = j + 8*half), j = 0..7, from
+    // the reformatted copy: element offset (kb32*CiB*TAPS + step)*512 + half*256 + l32*8 + j
+    const float *bbase = wd + (size_t)(k_ok ? kb32 : 0) * CiB * TAPS * 512 + half * 256 + l32 * 8;
+    auto load_b = [&](int s, float (&b)[8]) __attribute__((always_inline)) {
+        const float4 *p = reinterpret_cast<const float4 *>(bbase + (size_t)s * 512);
+        const float4 lo = p[0], hi = p[1];
+        b[0] = lo.x; b[1] = lo.y; b[2] = lo.z; b[3] = lo.w;
+        b[4] = hi.x; b[5] = hi.y; b[6] = hi.z; b[7] = hi.w;
+    };
     // A operand: lane supplies input (pixel = pb*32 + l32 of the tile, channels half*8 .. half*8+7)
     int apix[2];
 #pragma unroll
@@ -82,37 +91,48 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
         apix[pb] = (p / TW) * HW + (p % TW);
     }
 
-    for (int cb = 0; cb < CiB; ++cb) {
-        __builtin_amdgcn_wave_barrier();
+    // halo staging: the KQ wavefronts of a tile split its HP*4 float4 among their KQ*64 lanes
+    const int sl = kqi * kWave + lane;
+    auto load_halo = [&](int cb, float4 (&h)[NLD]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int jj = 0; jj < (HP * 4 + 63) / 64; ++jj) {
-            const int idx = jj * kWave + lane;
+        for (int jj = 0; jj < NLD; ++jj) {
+            const int idx = jj * (KQ * kWave) + sl;
             const int pix = idx >> 2, q = idx & 3;
-            if (pix < HP) {
-                const int a = pix / HW, b = pix % HW;
-                const int ih = ih0 + a, iw = iw0 + b;
-                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi)
-                    val = *reinterpret_cast<const float4 *>(in + act_off(n, cb, ih, iw, CiB, g.Hi, g.Wi) + q * 4);
-                *reinterpret_cast<float4 *>(lds + pix * XST + q * 4) = val;
-            }
+            const int a = pix / HW, b = pix % HW;
+            const int ih = ih0 + a, iw = iw0 + b;
+            h[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (tile_ok && pix < HP && ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi)
+                h[jj] = *reinterpret_cast<const float4 *>(in + act_off(n, cb, ih, iw, CiB, g.Hi, g.Wi) + q * 4);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto store_halo = [&](float *buf, const float4 (&h)[NLD]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < NLD; ++jj) {
+            const int idx = jj * (KQ * kWave) + sl;
+            const int pix = idx >> 2, q = idx & 3;
+            if (pix < HP) *reinterpret_cast<float4 *>(buf + pix * XST + q * 4) = h[jj];
+        }
+    };
 
+    constexpr int kWaitOlder = 2 | (0x7 << 4) | (0xF << 8);       // vmcnt(2): all but the 2 newest loads
+    const int nsteps = CiB * TAPS;
+    float bcur[8], bnxt[8];
+    float4 hreg[NLD];
+    load_halo(0, hreg);
+    store_halo(lds_all[0][tqi], hreg);
+    load_b(0, bcur);
+    __syncthreads();
+
+    for (int cb = 0; cb < CiB; ++cb) {
+        const float *lds = lds_all[cb & 1][tqi];
 #pragma unroll
         for (int v = 0; v < S; ++v)
 #pragma unroll
             for (int u = 0; u < R; ++u) {
-                const int tap = v * R + u;
-                float a[2][8], b[2][8];
-#pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2) {
-                    const float *p = fp[kb2] + ((size_t)cb * (S * R) + tap) * (kBlk * kBlk);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) b[kb2][j] = p[j * kBlk];
-                }
+                const int step = cb * TAPS + v * R + u;
+                load_b(min(step + 1, nsteps - 1), bnxt);        // next step's filters fly during this step's MFMAs
+                __builtin_amdgcn_sched_barrier(0);              // keep these loads ahead of the MFMAs below
+                float a[2][8];
 #pragma unroll
                 for (int pb = 0; pb < 2; ++pb) {
                     const float *p = lds + (apix[pb] + v * HW + u) * XST + half * 8;
@@ -121,22 +141,31 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
                     a[pb][0] = lo.x; a[pb][1] = lo.y; a[pb][2] = lo.z; a[pb][3] = lo.w;
                     a[pb][4] = hi.x; a[pb][5] = hi.y; a[pb][6] = hi.z; a[pb][7] = hi.w;
                 }
+                __builtin_amdgcn_s_waitcnt(kWaitOlder);         // bcur (and anything older) has arrived
+                __builtin_amdgcn_sched_barrier(0);
+                // The next block's halo is requested here, after the wait, so that the first wait
+                // that covers these loads is the one of the next tap: they land during the MFMAs.
+                if (v == 0 && u == 0 && cb + 1 < CiB) {
+                    load_halo(cb + 1, hreg);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (active) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
+                    for (int j = 0; j < 8; ++j)
 #pragma unroll
-                    for (int pb = 0; pb < 2; ++pb)
+                        for (int pb = 0; pb < 2; ++pb)
+                            acc[pb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[pb][j], bcur[j], acc[pb], 0, 0, 0);
+                }
 #pragma unroll
-                        for (int kb2 = 0; kb2 < 2; ++kb2)
-                            acc[pb][kb2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[pb][j], b[kb2][j],
-                                                                               acc[pb][kb2], 0, 0, 0);
+                for (int j = 0; j < 8; ++j) bcur[j] = bnxt[j];
             }
+        if (cb + 1 < CiB) store_halo(lds_all[(cb + 1) & 1][tqi], hreg);
+        __syncthreads();
     }
 
     // D layout of the 32x32 block: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
-#pragma unroll
-    for (int kb2 = 0; kb2 < 2; ++kb2) {
-        if (!kact[kb2]) continue;
-        const int k = kt * Cfg::KT + kb2 * 32 + l32;
+    const int k = kb32 * 32 + l32;
+    if (active && k < g.Ko) {
         const int kb = k / kBlk, ki = k % kBlk;
 #pragma unroll
         for (int pb = 0; pb < 2; ++pb)
@@ -145,23 +174,67 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
                 const int p = pb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
                 const int oh = oh0 + p / TW, ow = ow0 + p % TW;
                 if (oh < g.Ho && ow < g.Wo)
-                    out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[pb][kb2][r];
+                    out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[pb][r];
             }
     }
 }
 
-template <int R, int S>
-hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+// Prologue: filters in MFMA consumption order.  transpose = 0: B[k][c][tap] = w[k][c][tap] (FWD);
+// transpose = 1: the roles of the channel dimensions are swapped and the taps reversed, i.e. the
+// filters of the correlation that computes BWI (SparseTrain Sec. 3.3).  Ko/Ci are the output and
+// reduced channel counts of the correlation that will consume the copy; output channels are
+// padded with zeros to a multiple of 128.
+__global__ __launch_bounds__(256) void reformat_filters_kernel(int Ko, int Ci, int S, int R, int transpose,
+                                                               const float *__restrict__ w,
+                                                               float *__restrict__ wd, size_t total)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int TAPS = S * R, CiB = Ci / kBlk;
+    size_t t = i;
+    const int j = t % 8; t /= 8;
+    const int l32 = t % 32; t /= 32;
+    const int half = t % 2; t /= 2;
+    const int tap = t % TAPS; t /= TAPS;
+    const int cb = t % CiB;
+    const int kb32 = (int)(t / CiB);
+    const int ko = kb32 * 32 + l32, ci = cb * kBlk + half * 8 + j;
+    float val = 0.f;
+    if (ko < Ko) {
+        const int v = tap / R, u = tap % R;
+        if (!transpose) {
+            // w[K = Ko][C = Ci]: element [ko/16][ci/16][v][u][ci%16][ko%16]
+            val = w[((((size_t)(ko / kBlk) * CiB + ci / kBlk) * S + v) * R + u) * (kBlk * kBlk) + (ci % kBlk) * kBlk + ko % kBlk];
+        } else {
+            // w[K = Ci][C = Ko]: element [ci/16][ko/16][S-1-v][R-1-u][ko%16][ci%16]
+            const int KoB = Ko / kBlk;
+            val = w[((((size_t)(ci / kBlk) * KoB + ko / kBlk) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) + (ko % kBlk) * kBlk + ci % kBlk];
+        }
+    }
+    wd[i] = val;
+}
+
+template <int R, int S, int KQ>
+hipError_t launch_cfg(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
     using Cfg = FwdDenseCfg<R, S>;
+    constexpr int TQ = 4 / KQ;
     const int tiles_w = ceil_div(g.Wo, Cfg::TW), tiles_h = ceil_div(g.Ho, Cfg::TH);
-    const int ktiles = ceil_div(g.Ko, Cfg::KT);
-    const long long total = (long long)tiles_w * tiles_h * ktiles * g.N;
-    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((total + Cfg::WAVES - 1) / Cfg::WAVES));
-    hipLaunchKernelGGL((fwd_dense_kernel<R, S>), grid, dim3(256), 0, s, g, in, f, out, tiles_w, tiles_h,
-                       ktiles, (int)total);
+    const long long total_tiles = (long long)tiles_w * tiles_h * g.N;
+    const int kgroups = ceil_div(g.Ko, 32 * KQ);
+    const long long blocks = (total_tiles + TQ - 1) / TQ * kgroups;
+    if (total_tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ>), dim3((unsigned)blocks), dim3(256), 0, s, g, in, wd, out,
+                       tiles_w, tiles_h, kgroups, (int)total_tiles);
     return hipGetLastError();
+}
+
+template <int R, int S>
+hipError_t launch_rs(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
+{
+    if (g.Ko > 64) return launch_cfg<R, S, 4>(g, in, wd, out, s);
+    if (g.Ko > 32) return launch_cfg<R, S, 2>(g, in, wd, out, s);
+    return launch_cfg<R, S, 1>(g, in, wd, out, s);
 }
 
 }  // namespace
@@ -174,10 +247,24 @@ bool fwd_dense_supported(const Geom &g)
     return false;
 }
 
-hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+size_t fwd_dense_filter_bytes(const Geom &g)
 {
-    if (g.R == 3 && g.S == 3) return launch_cfg<3, 3>(g, in, f, out, s);
-    if (g.R == 1 && g.S == 1) return launch_cfg<1, 1>(g, in, f, out, s);
+    // output channels padded to a multiple of 128 so that every column block a workgroup touches exists
+    return (size_t)ceil_div(g.Ko, 128) * 128 * g.Ci * g.S * g.R * sizeof(float);
+}
+
+hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w, float *wd, hipStream_t s)
+{
+    const size_t total = fwd_dense_filter_bytes(g) / sizeof(float);
+    hipLaunchKernelGGL(reformat_filters_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, g.Ko, g.Ci,
+                       g.S, g.R, transpose ? 1 : 0, w, wd, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
+{
+    if (g.R == 3 && g.S == 3) return launch_rs<3, 3>(g, in, wd, out, s);
+    if (g.R == 1 && g.S == 1) return launch_rs<1, 1>(g, in, wd, out, s);
     return hipErrorInvalidValue;
 }
 
