@@ -45,7 +45,10 @@ struct FwdSparseCfg {
     static constexpr int KT = 64 * KPL;                     // output channels per wavefront
 };
 
-template <int R, int S, int TH, int TW, int KPL, int MINW>
+// CS = number of wavefronts that share one task, each reducing 1/CS of the input channels; their
+// partial tiles are added through LDS at the end (in a fixed order).  CS > 1 multiplies the
+// number of wavefronts of a layer with few tiles without shrinking the tile.
+template <int R, int S, int TH, int TW, int KPL, int MINW, int CS>
 __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
                                                          const float *__restrict__ f,
                                                          float *__restrict__ out,
@@ -56,11 +59,12 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][kBlk * PST];
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int wid = blockIdx.x * Cfg::WAVES + wave;
-    if (wid >= total) return;                       // whole wavefront leaves; no block barrier is used
+    const int cpart = wave % CS;                    // which share of the input channels
+    const int wid = blockIdx.x * (Cfg::WAVES / CS) + wave / CS;
+    const bool valid = wid < total;                 // an invalid wavefront only takes part in barriers
     float *lds = lds_all[wave];
 
-    int t = wid;
+    int t = valid ? wid : 0;
     const int kt = t % ktiles; t /= ktiles;
     const int tw = t % tiles_w; t /= tiles_w;
     const int th = t % tiles_h;
@@ -158,15 +162,17 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 
     // Two filter register sets alternate: the loads for channel c+1 are in flight while the
     // multiply-adds of channel c run, so the L2 latency of the filter stream is hidden.
+    const int cb_begin = cpart * (CiB / CS), cb_end = cb_begin + CiB / CS;      // CiB % CS == 0
+    const int c_last = cb_end * kBlk - 1;
     float wA[KPL][S * R], wB[KPL][S * R];
-    load_w(0, wA);
+    load_w(cb_begin * kBlk, wA);
     // s_waitcnt vmcnt(NW) with the other counters left at their maxima: vector loads return in
     // order, so this waits for everything older than the NW most recent loads (one filter set).
     constexpr int NW = KPL * S * R;
     static_assert(NW < 64, "vmcnt is a 6-bit counter");
     constexpr int kWaitOlderSet = (NW & 0xF) | ((NW >> 4) << 14) | (0x7 << 4) | (0xF << 8);
 
-    for (int cb = 0; cb < CiB; ++cb) {
+    for (int cb = valid ? cb_begin : cb_end; cb < cb_end; ++cb) {
         // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -194,44 +200,91 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
             load_w(c + 1, wB);
             __builtin_amdgcn_s_waitcnt(kWaitOlderSet);     // wA has arrived; wB stays in flight
             process(ci, wA);
-            load_w(min(c + 2, g.Ci - 1), wA);
+            load_w(min(c + 2, c_last), wA);
             __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
             process(ci + 1, wB);
         }
     }
 
+    // ---- add the partial tiles of the CS wavefronts of a task (fixed order: share 0 + 1 + ...) ----
+    if constexpr (CS > 1) {
+        constexpr int NACC = KPL * TH * TW, CHUNK = 16;
+        static_assert(NACC % CHUNK == 0 && CHUNK * kWave <= kBlk * PST, "reduction chunk must fit the staging region");
+#pragma unroll
+        for (int c0 = 0; c0 < NACC; c0 += CHUNK) {
+            __syncthreads();                        // the staging region / previous chunk is no longer read
+            if (cpart != 0) {
+#pragma unroll
+                for (int i = 0; i < CHUNK; ++i) lds[i * kWave + lane] = acc[(c0 + i) / (TH * TW)][(c0 + i) % (TH * TW)];
+            }
+            __syncthreads();
+            if (cpart == 0) {
+#pragma unroll
+                for (int pp = 1; pp < CS; ++pp)
+#pragma unroll
+                    for (int i = 0; i < CHUNK; ++i)
+                        acc[(c0 + i) / (TH * TW)][(c0 + i) % (TH * TW)] += lds_all[wave + pp][i * kWave + lane];
+            }
+        }
+    }
+
     // ---- store the tile ----
+    if (valid && cpart == 0) {
 #pragma unroll
-    for (int j = 0; j < KPL; ++j) {
-        if (!kact[j]) continue;
-        const int k = kt * Cfg::KT + j * kWave + lane;
-        const int kb = k / kBlk, ki = k % kBlk;
+        for (int j = 0; j < KPL; ++j) {
+            if (!kact[j]) continue;
+            const int k = kt * Cfg::KT + j * kWave + lane;
+            const int kb = k / kBlk, ki = k % kBlk;
 #pragma unroll
-        for (int a = 0; a < TH; ++a) {
-            const int oh = oh0 + a;
-            if (oh >= g.Ho) continue;
+            for (int a = 0; a < TH; ++a) {
+                const int oh = oh0 + a;
+                if (oh >= g.Ho) continue;
 #pragma unroll
-            for (int b = 0; b < TW; ++b) {
-                const int ow = ow0 + b;
-                if (ow >= g.Wo) continue;
-                out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[j][a * TW + b];
+                for (int b = 0; b < TW; ++b) {
+                    const int ow = ow0 + b;
+                    if (ow >= g.Wo) continue;
+                    out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[j][a * TW + b];
+                }
             }
         }
     }
 }
 
-template <int R, int S, int TH, int TW, int KPL, int MINW>
-hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+template <int R, int S, int TH, int TW, int KPL, int MINW, int CS>
+hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
     const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
     const int ktiles = ceil_div(g.Ko, Cfg::KT);
     const long long total = (long long)tiles_w * tiles_h * ktiles * g.N;
     if (total > 0x7fffffffLL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((total + Cfg::WAVES - 1) / Cfg::WAVES));
-    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW>), grid, dim3(256), 0, s, g, in, f, out,
+    constexpr int per_wg = Cfg::WAVES / CS;
+    dim3 grid((unsigned)((total + per_wg - 1) / per_wg));
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS>), grid, dim3(256), 0, s, g, in, f, out,
                        tiles_w, tiles_h, ktiles, (int)total);
     return hipGetLastError();
+}
+
+// Picks the channel split: layers with few tiles get 2 or 4 wavefronts per task so that the chip
+// (1024 SIMDs x 4 resident wavefronts) is filled and the tail is short.  ST_FWD_SPARSE_CS
+// overrides (tuning aid).
+template <int R, int S, int TH, int TW, int KPL, int MINW>
+hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+{
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
+    const long long tasks = (long long)ceil_div(g.Wo, TW) * ceil_div(g.Ho, TH) * ceil_div(g.Ko, Cfg::KT) * g.N;
+    const int CiB = g.Ci / kBlk;
+    int cs = 1;
+    if (CiB >= 4 && CiB % 2 == 0) cs = 2;
+    if ((CiB >= 16 || tasks < 3072) && CiB % 4 == 0) cs = 4;
+    const char *env = getenv("ST_FWD_SPARSE_CS");
+    if (env) {
+        const int e = atoi(env);
+        if ((e == 1 || e == 2 || e == 4) && CiB % e == 0) cs = e;
+    }
+    if (cs == 4) return launch_cs<R, S, TH, TW, KPL, MINW, 4>(g, in, f, out, s);
+    if (cs == 2) return launch_cs<R, S, TH, TW, KPL, MINW, 2>(g, in, f, out, s);
+    return launch_cs<R, S, TH, TW, KPL, MINW, 1>(g, in, f, out, s);
 }
 
 }  // namespace
@@ -246,25 +299,15 @@ bool fwd_sparse_supported(const Geom &g)
 
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
-    // ST_FWD_SPARSE_CFG selects a tile configuration by hand (tuning aid); unset = heuristic.
-    const char *env = getenv("ST_FWD_SPARSE_CFG");
-    const int cfg = env ? atoi(env) : 0;
+    // 64 accumulators per lane (4x8 pixels x 2 channels, or 8x8 pixels x 1 channel) keep the
+    // kernel within 128 registers, i.e. 4 wavefronts per SIMD.
+    const bool wide = g.Ko % 128 == 0;
     if (g.R == 3 && g.S == 3) {
-        const bool wide = g.Ko % 128 == 0;
-        switch (cfg) {
-        case 1: return launch_cfg<3, 3, 8, 8, 1, 3>(g, in, f, out, s);
-        case 2: if (wide) return launch_cfg<3, 3, 4, 8, 2, 4>(g, in, f, out, s); break;
-        case 3: return launch_cfg<3, 3, 4, 8, 1, 4>(g, in, f, out, s);
-        case 4: return launch_cfg<3, 3, 8, 8, 1, 4>(g, in, f, out, s);
-        case 5: if (wide) return launch_cfg<3, 3, 4, 8, 2, 3>(g, in, f, out, s); break;
-        default: break;
-        }
-        if (cfg == 6 && wide) return launch_cfg<3, 3, 8, 8, 2, 2>(g, in, f, out, s);
         if (wide) return launch_cfg<3, 3, 4, 8, 2, 4>(g, in, f, out, s);
-        return launch_cfg<3, 3, 4, 8, 1, 4>(g, in, f, out, s);
+        return launch_cfg<3, 3, 8, 8, 1, 4>(g, in, f, out, s);
     }
     if (g.R == 1 && g.S == 1) {
-        if (g.Ko % 128 == 0) return launch_cfg<1, 1, 8, 8, 2, 2>(g, in, f, out, s);
+        if (wide) return launch_cfg<1, 1, 8, 8, 2, 2>(g, in, f, out, s);
         return launch_cfg<1, 1, 8, 8, 1, 4>(g, in, f, out, s);
     }
     return hipErrorInvalidValue;
