@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the 0-90 %% zero-fraction sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--sweep-iters", type=int, default=5)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy kernel (reference for rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one MI355X per box); --gpus must be 1",
@@ -92,6 +95,14 @@ def main():
         run_pass("fwd", False)
         run_pass("bwi", False)
         run_pass("bww", False)
+
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)              # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: W warm-up steps, then exactly K steps ----
     for _ in range(args.warmup):

@@ -157,10 +157,10 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
                 const unsigned mw = (j < 2) ? mlo : mhi;
                 constexpr int sh = (j % 2) * 16;
                 const unsigned bits = (mw >> sh) >> (h * CH) & 0xFFu;     // this wave's 8 channels
-                if (bits) {
+                if (__builtin_expect(bits != 0u, 1)) {
                     static_for<0, CH>([&](auto CI) __attribute__((always_inline)) {
                         constexpr int ci = decltype(CI)::value;
-                        if (bits & (1u << ci)) {
+                        if (__builtin_expect((bits & (1u << ci)) != 0u, 1)) {
 #pragma unroll
                             for (int v = 0; v < S; ++v)
 #pragma unroll

@@ -119,26 +119,27 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
         // newest read have arrived".
         const float4 *lds4 = reinterpret_cast<const float4 *>(lds + ci * PST);
         constexpr int NG = (HP + 3) / 4;
-        float4 cur = lds4[0];
+        float4 xq[2];                       // two groups of values alternate (no register copies)
+        xq[0] = lds4[0];
         static_for<0, NG>([&](auto G) __attribute__((always_inline)) {
             constexpr int gidx = decltype(G)::value;
-            float4 nxt = cur;
             if constexpr (gidx + 1 < NG) {
-                nxt = lds4[gidx + 1];
+                xq[(gidx + 1) % 2] = lds4[gidx + 1];
                 __builtin_amdgcn_s_waitcnt(0xC17F);      // lgkmcnt(1)
             } else {
                 __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
             }
+            const float4 cur = xq[gidx % 2];
             const float xg[4] = {cur.x, cur.y, cur.z, cur.w};
             // a group whose four pixels are all zero costs one test instead of four
             constexpr unsigned gmask = 0xFu << ((gidx * 4) % 32);
-            if (m32[(gidx * 4) / 32] & gmask)
+            if (__builtin_expect((m32[(gidx * 4) / 32] & gmask) != 0u, 1))
             // one branch per halo pixel; all register indices below are compile-time constants
             static_for<0, 4>([&](auto J) __attribute__((always_inline)) {
                 constexpr int i = gidx * 4 + decltype(J)::value;
                 if constexpr (i < HP) {
                     constexpr int a = i / HW, b = i % HW;
-                    if (m32[i / 32] & (1u << (i % 32))) {
+                    if (__builtin_expect((m32[i / 32] & (1u << (i % 32))) != 0u, 1)) {
                         const float xs = xg[i % 4];
 #pragma unroll
                         for (int v = 0; v < S; ++v) {
@@ -156,12 +157,23 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
                     }
                 }
             });
-            cur = nxt;
         });
     };
 
     // Two filter register sets alternate: the loads for channel c+1 are in flight while the
     // multiply-adds of channel c run, so the L2 latency of the filter stream is hidden.
+    // Halo staging: lane -> (pixel, channel quarter) slots; the element offset of each slot inside
+    // one (image, channel block) plane is fixed for the whole task (-1 = outside the image).
+    constexpr int NST = (HP * 4 + 63) / 64;
+    int soff[NST];
+#pragma unroll
+    for (int jj = 0; jj < NST; ++jj) {
+        const int idx = jj * kWave + lane;
+        const int pix = idx >> 2, q = idx & 3;
+        const int ih = ih0 + pix / HW, iw = iw0 + pix % HW;
+        soff[jj] = (pix < HP && ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi) ? (ih * g.Wi + iw) * kBlk + q * 4 : -1;
+    }
+
     const int cb_begin = cpart * (CiB / CS), cb_end = cb_begin + CiB / CS;      // CiB % CS == 0
     const int c_last = cb_end * kBlk - 1;
     float wA[KPL][S * R], wB[KPL][S * R];
@@ -175,20 +187,20 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     for (int cb = valid ? cb_begin : cb_end; cb < cb_end; ++cb) {
         // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----
         __builtin_amdgcn_wave_barrier();
+        {
+            const float *plane = in + act_off(n, cb, 0, 0, CiB, g.Hi, g.Wi);      // wave-uniform base
 #pragma unroll
-        for (int jj = 0; jj < (HP * 4 + 63) / 64; ++jj) {
-            const int idx = jj * kWave + lane;
-            const int pix = idx >> 2, q = idx & 3;
-            if (pix < HP) {
-                const int a = pix / HW, b = pix % HW;
-                const int ih = ih0 + a, iw = iw0 + b;
-                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi)
-                    val = *reinterpret_cast<const float4 *>(in + act_off(n, cb, ih, iw, CiB, g.Hi, g.Wi) + q * 4);
-                lds[(q * 4 + 0) * PST + pix] = val.x;
-                lds[(q * 4 + 1) * PST + pix] = val.y;
-                lds[(q * 4 + 2) * PST + pix] = val.z;
-                lds[(q * 4 + 3) * PST + pix] = val.w;
+            for (int jj = 0; jj < NST; ++jj) {
+                const int idx = jj * kWave + lane;
+                const int pix = idx >> 2, q = idx & 3;
+                if (pix < HP) {
+                    float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (soff[jj] >= 0) val = *reinterpret_cast<const float4 *>(plane + soff[jj]);
+                    lds[(q * 4 + 0) * PST + pix] = val.x;
+                    lds[(q * 4 + 1) * PST + pix] = val.y;
+                    lds[(q * 4 + 2) * PST + pix] = val.z;
+                    lds[(q * 4 + 3) * PST + pix] = val.w;
+                }
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

@@ -53,6 +53,10 @@ SMALL = [
     # fewer channels than lanes
     ("3x3_k16", Geom(3, 16, 16, 10, 7, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
     ("3x3_k48_c80", Geom(1, 80, 48, 11, 12, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    # channel split across the wavefronts of a workgroup: 2 shares (6 channel blocks), 4 shares
+    ("3x3_c96_split2", Geom(1, 96, 128, 9, 9, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    ("3x3_c64_k64_split4", Geom(2, 64, 64, 10, 13, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    ("3x3_c256_k128_split4", Geom(1, 256, 128, 6, 7, 3, 3, 1, 1, 1, 1), 0.6, 0.6),
     # other paddings of the 3x3 fast path
     ("3x3_pad0", Geom(2, 32, 64, 12, 14, 3, 3, 1, 1, 0, 0), 0.5, 0.5),
     ("3x3_pad2_1", Geom(1, 32, 64, 9, 10, 3, 3, 1, 1, 2, 1), 0.5, 0.5),
