@@ -25,9 +25,10 @@ PEAK_FP32_VECTOR = 157.3      # TFLOP/s, published MI355X fp32 vector peak (need
 PEAK_FP32_FMA = 78.6          # TFLOP/s, 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz: one v_fma_f32 per lane-clock
 PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
 
-# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured for the kernel in this tree.
-MEASURED_TRAFFIC_BYTES = None
+# HBM traffic per launch of the dominant kernel (fwd_sparse_kernel on this workload) from two
+# rocprofv3 --pmc runs, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 (factors from a 256 MiB copy of known
+# size): 211076.1 KiB * 2 + 134848.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = int((211076.1 * 2.0 + 134848.0) * 1024)
 
 
 def main():
@@ -153,12 +154,13 @@ def main():
     fwd_avg_ms = passes["fwd"]["sparse_avg_ms"]
     achieved = F * (1 - px) / (fwd_avg_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4> (st_conv_fwd; st_conv_bwi runs the same kernel on dy)",
+        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4,4> (st_conv_fwd; st_conv_bwi runs the same kernel on dy)",
         "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_FP32_VECTOR, 4),
         "peak_unpacked_fma": PEAK_FP32_FMA, "frac_of_unpacked_fma_peak": round(achieved / PEAK_FP32_FMA, 4),
         "avg_launch_ms": fwd_avg_ms, "algorithmic_flops_per_launch": F * (1 - px),
-        "traffic": MEASURED_TRAFFIC_BYTES, "slowest_pass": dom,
+        "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes_per_launch": 4 * (x_h.size + w_h.size + x_h.size * L.K // L.C),
+        "slowest_pass": dom,
     }
 
     # ---- sparse-over-dense speedup at 0-90 % zeros ----
