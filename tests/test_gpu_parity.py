@@ -155,6 +155,54 @@ def test_config5_vgg_late_layers(layer):
         check_all_passes_sampled(g, x, w, dy, "config5-" + layer.name, n_samples=2048, n_bww=256)
 
 
+def test_config5_vgg1_2_full_size_sampled():
+    """The largest layer of the VGG16 stack (N=32, 64->64 @224x224, 411 MB per activation tensor):
+    exercises the 64-channel tile configuration, 25088 tiles per pass and 64-bit offsets."""
+    layer = stgen.vgg16_stack(0.5)[0]
+    assert layer.name == "vgg1_2" and layer.N == 32
+    g = geom_of(layer)
+    x, w, dy = stgen.make_layer_tensors(layer, seed=3)
+    check_all_passes_sampled(g, x, w, dy, "config5-vgg1_2", n_samples=4096, n_bww=128)
+
+
+@pytest.mark.parametrize("name,p", [("vgg2_1", 0.3), ("vgg2_2", 0.7), ("vgg3_1", 0.5), ("vgg3_2", 0.9),
+                                    ("vgg4_3", 0.0), ("vgg5_2", 0.7)])
+def test_config5_vgg_layers_full_batch_sampled(name, p):
+    """The other VGG16 layer shapes at the full minibatch N=32, one swept zero fraction each."""
+    layer = [l for l in stgen.vgg16_stack(p) if l.name == name][0]
+    g = geom_of(layer)
+    x, w, dy = stgen.make_layer_tensors(layer, seed=4)
+    check_all_passes_sampled(g, x, w, dy, f"config5-{name}-p{p}", n_samples=2048, n_bww=128)
+
+
+def test_side_stream_and_reused_workspace():
+    """Calls on a non-default stream with one workspace reused by consecutive calls give the same
+    bits as calls on the default stream (the library only enqueues; it never synchronises)."""
+    g = Geom(2, 64, 128, 16, 16, 3, 3, 1, 1, 1, 1)
+    x, w, dy = synth(g, 0.5, 0.5, seed=11)
+    L = DeviceLayer(g, x, w, dy)
+    ref_y, ref_dx, ref_dw = L.fwd(False), L.bwi(False), L.bww(False)
+    d = L.d
+    need = max(st.st_conv_workspace_bytes(d, p, dn) for p in (0, 1, 2) for dn in (False, True))
+    side = torch.cuda.Stream()
+    ws = torch.empty(need // 4 + 64, dtype=torch.float32, device="cuda")
+    y = torch.empty((g.N, g.K // 16, g.OH, g.OW, 16), device="cuda")
+    dx = torch.empty((g.N, g.C // 16, g.H, g.W, 16), device="cuda")
+    dw = torch.empty((g.K // 16, g.C // 16, g.S, g.R, 16, 16), device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            st.st_conv_fwd(d, L.x, L.w, y, ws, side)
+            st.st_conv_bwi(d, L.dy, L.w, dx, ws, side)
+            st.st_conv_bww(d, L.x, L.dy, dw, ws, side)
+            st.st_conv_fwd_dense(d, L.x, L.w, y, ws, side)
+            st.st_conv_fwd(d, L.x, L.w, y, ws, side)
+    side.synchronize()
+    assert np.array_equal(st.unpack_activations(y.cpu().numpy()), ref_y)
+    assert np.array_equal(st.unpack_activations(dx.cpu().numpy()), ref_dx)
+    assert np.array_equal(st.unpack_filters(dw.cpu().numpy()), ref_dw)
+
+
 @pytest.mark.parametrize("p", [0.0, 0.3, 0.7, 0.9])
 def test_config5_sweep_levels_on_vgg5(p):
     layer = stgen.vgg16_stack(p, n=8)[-1]
