@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256) void bww_reduce_kernel(const float4 *__restric
 }
 
 constexpr int kSparseTH = 8, kSparseTW = 8;
-constexpr int kDenseTH = 8, kDenseTW = 16;
+constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
 
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 {
