@@ -29,24 +29,26 @@ __device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, i
     return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
 }
 
-template <int R, int S>
+// TWD = tile width: 8 (8 rows), 14 (4 rows) or 28 (2 rows); a tile holds at most 64 pixels, i.e.
+// two 32-row MFMA blocks; with 14 or 28 columns the last 8 rows of the second block are padding.
+template <int R, int S, int TWD>
 struct FwdDenseCfg {
-    static constexpr int TH = 8, TW = 8;
+    static constexpr int TW = TWD, TH = 64 / TWD, NPIX = TH * TW;
     static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
     static constexpr int XST = 20;                  // floats per staged pixel (16 channels + 4 pad)
     static constexpr int BUF = ((HP * XST + 63) / 64) * 64;   // floats per halo buffer
 };
 
 // KQ = column blocks (of 32 output channels) per workgroup: 1, 2 or 4; TQ = 4/KQ pixel tiles.
-template <int R, int S, int KQ>
+template <int R, int S, int KQ, int TWD>
 __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *__restrict__ in,
                                                            const float *__restrict__ wd,
                                                            float *__restrict__ out, int tiles_w,
                                                            int tiles_h, int kgroups, int total_tiles)
 {
-    using Cfg = FwdDenseCfg<R, S>;
+    using Cfg = FwdDenseCfg<R, S, TWD>;
     constexpr int TH = Cfg::TH, TW = Cfg::TW, HW = Cfg::HW, HP = Cfg::HP, XST = Cfg::XST, BUF = Cfg::BUF;
-    constexpr int TAPS = S * R, TQ = 4 / KQ;
+    constexpr int TAPS = S * R, TQ = 4 / KQ, NPIX = Cfg::NPIX;
     constexpr int NLD = (HP * 4 + KQ * 64 - 1) / (KQ * 64);      // float4 loads per lane and block
     __shared__ __attribute__((aligned(16))) float lds_all[2][TQ][BUF];
 
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
     int apix[2];
 #pragma unroll
     for (int pb = 0; pb < 2; ++pb) {
-        const int p = pb * 32 + l32;
+        const int p = min(pb * 32 + l32, NPIX - 1);        // padding rows read a valid pixel; never stored
         apix[pb] = (p / TW) * HW + (p % TW);
     }
 
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
             for (int r = 0; r < 16; ++r) {
                 const int p = pb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
                 const int oh = oh0 + p / TW, ow = ow0 + p % TW;
-                if (oh < g.Ho && ow < g.Wo)
+                if (p < NPIX && oh < g.Ho && ow < g.Wo)
                     out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[pb][r];
             }
     }
@@ -214,27 +216,36 @@ __global__ __launch_bounds__(256) void reformat_filters_kernel(int Ko, int Ci, i
     wd[i] = val;
 }
 
-template <int R, int S, int KQ>
+template <int R, int S, int KQ, int TWD>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
-    using Cfg = FwdDenseCfg<R, S>;
+    using Cfg = FwdDenseCfg<R, S, TWD>;
     constexpr int TQ = 4 / KQ;
     const int tiles_w = ceil_div(g.Wo, Cfg::TW), tiles_h = ceil_div(g.Ho, Cfg::TH);
     const long long total_tiles = (long long)tiles_w * tiles_h * g.N;
     const int kgroups = ceil_div(g.Ko, 32 * KQ);
     const long long blocks = (total_tiles + TQ - 1) / TQ * kgroups;
     if (total_tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ>), dim3((unsigned)blocks), dim3(256), 0, s, g, in, wd, out,
+    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ, TWD>), dim3((unsigned)blocks), dim3(256), 0, s, g, in, wd, out,
                        tiles_w, tiles_h, kgroups, (int)total_tiles);
     return hipGetLastError();
+}
+
+template <int R, int S, int TWD>
+hipError_t launch_kq(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
+{
+    if (g.Ko > 64) return launch_cfg<R, S, 4, TWD>(g, in, wd, out, s);
+    if (g.Ko > 32) return launch_cfg<R, S, 2, TWD>(g, in, wd, out, s);
+    return launch_cfg<R, S, 1, TWD>(g, in, wd, out, s);
 }
 
 template <int R, int S>
 hipError_t launch_rs(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
-    if (g.Ko > 64) return launch_cfg<R, S, 4>(g, in, wd, out, s);
-    if (g.Ko > 32) return launch_cfg<R, S, 2>(g, in, wd, out, s);
-    return launch_cfg<R, S, 1>(g, in, wd, out, s);
+    // tile width that divides the row length, if any: 8 -> 8x8, 28 -> 2x28, 14 -> 4x14
+    if (g.Wo % 8 != 0 && g.Wo % 28 == 0 && g.Ho % 2 == 0) return launch_kq<R, S, 28>(g, in, wd, out, s);
+    if (g.Wo % 8 != 0 && g.Wo % 14 == 0 && g.Ho % 4 <= g.Ho % 8) return launch_kq<R, S, 14>(g, in, wd, out, s);
+    return launch_kq<R, S, 8>(g, in, wd, out, s);
 }
 
 }  // namespace

@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 
     // ---- add the partial tiles of the CS wavefronts of a task (fixed order: share 0 + 1 + ...) ----
     if constexpr (CS > 1) {
-        constexpr int NACC = KPL * TH * TW, CHUNK = 16;
+        constexpr int NACC = KPL * TH * TW, CHUNK = 8;
         static_assert(NACC % CHUNK == 0 && CHUNK * kWave <= kBlk * PST, "reduction chunk must fit the staging region");
 #pragma unroll
         for (int c0 = 0; c0 < NACC; c0 += CHUNK) {
@@ -315,8 +315,10 @@ hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, flo
     // kernel within 128 registers, i.e. 4 wavefronts per SIMD.
     const bool wide = g.Ko % 128 == 0;
     if (g.R == 3 && g.S == 3) {
-        if (wide) return launch_cfg<3, 3, 4, 8, 2, 4>(g, in, f, out, s);
-        return launch_cfg<3, 3, 8, 8, 1, 4>(g, in, f, out, s);
+        // 7-wide tiles when the row length is a multiple of 7 but not of 8 (28, 14): no ragged tiles
+        const bool seven = g.Wo % 8 != 0 && g.Wo % 7 == 0;
+        if (wide) return seven ? launch_cfg<3, 3, 4, 7, 2, 4>(g, in, f, out, s) : launch_cfg<3, 3, 4, 8, 2, 4>(g, in, f, out, s);
+        return seven ? launch_cfg<3, 3, 8, 7, 1, 4>(g, in, f, out, s) : launch_cfg<3, 3, 8, 8, 1, 4>(g, in, f, out, s);
     }
     if (g.R == 1 && g.S == 1) {
         if (wide) return launch_cfg<1, 1, 8, 8, 2, 2>(g, in, f, out, s);
