@@ -31,6 +31,78 @@ PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
 MEASURED_TRAFFIC_BYTES = int((211076.1 * 2.0 + 134848.0) * 1024)
 
 
+def write_config_table(path, st, stgen, torch, dev, stream):
+    """Per (layer, zero fraction, pass): sparse and dense time, effective TFLOP/s, executed TFLOP/s as a
+    fraction of the fp32 vector peak, dense fraction of the MFMA peak, speed-up.  Inputs are drawn on the
+    device (torch generator, seed 0) with the same distributions as stgen: timing only, no parity."""
+    import math
+
+    torch.manual_seed(0)
+
+    def relu_sparse(shape, p):
+        z = torch.randn(shape, device=dev)
+        if p <= 0:
+            return z
+        t = math.sqrt(2.0) * torch.erfinv(torch.tensor(2.0 * p - 1.0, dtype=torch.float64)).item()
+        return torch.clamp(z - t, min=0)
+
+    def masked(shape, q):
+        g = torch.randn(shape, device=dev)
+        return g if q <= 0 else g * (torch.rand(shape, device=dev) >= q)
+
+    def timeit(fn, iters=7):
+        fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for a, b in evs:
+            a.record(stream)
+            fn()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs)
+        return ts[len(ts) // 2]
+
+    rows = []
+
+    def run(cfg, L, px, pdy):
+        d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
+        x = relu_sparse((L.N, L.C // 16, L.H, L.W, 16), px)
+        dy = masked((L.N, L.K // 16, L.OH, L.OW, 16), pdy)
+        w = torch.randn((L.K // 16, L.C // 16, L.S, L.R, 16, 16), device=dev) * math.sqrt(2.0 / (L.C * L.R * L.S))
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        zx = float((x == 0).float().mean())
+        zdy = float((dy == 0).float().mean())
+
+        def ws(p, dn):
+            n = st.st_conv_workspace_bytes(d, p, dn)
+            return torch.empty(max(n // 4, 1), device=dev) if n else None
+
+        for name, fs, fd, a, b, o, pi, z in (("FWD", st.st_conv_fwd, st.st_conv_fwd_dense, x, w, y, 0, zx),
+                                             ("BWI", st.st_conv_bwi, st.st_conv_bwi_dense, dy, w, dx, 1, zdy),
+                                             ("BWW", st.st_conv_bww, st.st_conv_bww_dense, x, dy, dw, 2, zx)):
+            wss, wsd = ws(pi, False), ws(pi, True)
+            ts = timeit(lambda: fs(d, a, b, o, wss, stream))
+            td = timeit(lambda: fd(d, a, b, o, wsd, stream))
+            eff = d.flops / ts / 1e9
+            rows.append(f"| {cfg} | {L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S} N={L.N} | {name} | {z:.2f} | {ts * 1e3:.0f} | "
+                        f"{td * 1e3:.0f} | {eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | "
+                        f"{d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} |")
+        del x, dy, w, y, dx, dw
+
+    run(3, stgen.RESNET3_2, stgen.RESNET3_2.p_x, stgen.RESNET3_2.p_dy)
+    for L in stgen.BOTTLENECK:
+        run(4, L, L.p_x, L.p_dy)
+    for p in (0.0, 0.3, 0.5, 0.7, 0.9):
+        for L in stgen.vgg16_stack(p):
+            if L.name in ("vgg3_3", "vgg4_3", "vgg5_2", "vgg5_3"):      # same shapes as 3_2, 4_2, 5_1
+                continue
+            run(5, L, p, p)
+    with open(path, "w") as f:
+        f.write("| config | layer | pass | zeros of tested operand | sparse us | dense us | effective TFLOP/s | "
+                "executed / 157.3 (fp32 vector peak) | dense / 157.3 (MFMA peak) | speed-up |\n")
+        f.write("|---|---|---|---|---|---|---|---|---|---|\n")
+        f.write("\n".join(rows) + "\n")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,6 +111,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the 0-90 %% zero-fraction sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--sweep-iters", type=int, default=5)
+    ap.add_argument("--table", metavar="FILE", default=None,
+                    help="also time every other workload of the benchmark definition (ResNet-34 block, ResNet-50 "
+                         "bottleneck, VGG16 stack at 0-90 %% zeros) and write a markdown table to FILE")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy kernel (reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -204,6 +279,9 @@ def main():
         cpu = {"value": round(ff / tt / 1e12, 5), "unit": "TFLOP/s", "cores": st_ref.threads(), "kind": "oracle",
                "sample": f"FWD+BWI+BWW of the first {n_img} of {L.N} images of the same tensors, "
                          f"{tt:.2f} s of wall time; dense-equivalent flops / time"}
+
+    if args.table:
+        write_config_table(args.table, st, stgen, torch, dev, stream)
 
     out = {
         "metric": "effective conv TFLOP/s (FWD+BWI+BWW, zero-skipping entry points)",

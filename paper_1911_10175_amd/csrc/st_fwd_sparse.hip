@@ -220,7 +220,8 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 
     // ---- add the partial tiles of the CS wavefronts of a task (fixed order: share 0 + 1 + ...) ----
     if constexpr (CS > 1) {
-        constexpr int NACC = KPL * TH * TW, CHUNK = 8;
+        constexpr int NACC = KPL * TH * TW;
+        constexpr int CHUNK = (NACC % 8 == 0 && 8 * kWave <= kBlk * PST) ? 8 : (NACC % 4 == 0 && 4 * kWave <= kBlk * PST) ? 4 : 1;
         static_assert(NACC % CHUNK == 0 && CHUNK * kWave <= kBlk * PST, "reduction chunk must fit the staging region");
 #pragma unroll
         for (int c0 = 0; c0 < NACC; c0 += CHUNK) {
@@ -321,6 +322,9 @@ hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, flo
         return seven ? launch_cfg<3, 3, 8, 7, 1, 4>(g, in, f, out, s) : launch_cfg<3, 3, 8, 8, 1, 4>(g, in, f, out, s);
     }
     if (g.R == 1 && g.S == 1) {
+        // without spatial reuse a non-zero input feeds only KPL multiply-adds per lane: use as many
+        // output channels per lane as the layer has (Sec. 5.2 of the paper: T = Q/V for 1x1)
+        if (g.Ko % 256 == 0) return launch_cfg<1, 1, 2, 8, 4, 4>(g, in, f, out, s);
         if (wide) return launch_cfg<1, 1, 8, 8, 2, 2>(g, in, f, out, s);
         return launch_cfg<1, 1, 8, 8, 1, 4>(g, in, f, out, s);
     }
