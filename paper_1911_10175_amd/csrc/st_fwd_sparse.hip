@@ -52,7 +52,8 @@ template <int R, int S, int TH, int TW, int KPL, int MINW, int CS>
 __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
                                                          const float *__restrict__ f,
                                                          float *__restrict__ out,
-                                                         int tiles_w, int tiles_h, int ktiles, int total)
+                                                         int tiles_w, int tiles_h, int ktiles, int total,
+                                                               int slots_per_xcd)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
@@ -60,12 +61,19 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int cpart = wave % CS;                    // which share of the input channels
-    const int wid = blockIdx.x * (Cfg::WAVES / CS) + wave / CS;
-    const bool valid = wid < total;                 // an invalid wavefront only takes part in barriers
+    // Workgroup -> (tile slot, output-channel tile).  Consecutive workgroup ids are dealt round-robin
+    // to the 8 XCDs, each with its own L2; workgroups 8 ids apart run on the same XCD one after the
+    // other.  Every XCD gets a contiguous range of pixel tiles and walks it tile by tile, all
+    // output-channel tiles of a pixel tile first: the input halo shared by those workgroups, and the
+    // halo columns shared with the next pixel tile, are fetched into that L2 once.
+    constexpr int TPW = Cfg::WAVES / CS;            // tasks (pixel tiles) per workgroup
+    const int xcd = blockIdx.x % 8, seq = blockIdx.x / 8;
+    const int kt = seq % ktiles;
+    const int tile = (xcd * slots_per_xcd + seq / ktiles) * TPW + wave / CS;
+    const bool valid = tile < total;                // an invalid wavefront only takes part in barriers
     float *lds = lds_all[wave];
 
-    int t = valid ? wid : 0;
-    const int kt = t % ktiles; t /= ktiles;
+    int t = valid ? tile : 0;
     const int tw = t % tiles_w; t /= tiles_w;
     const int th = t % tiles_h;
     const int n = t / tiles_h;
@@ -162,17 +170,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 
     // Two filter register sets alternate: the loads for channel c+1 are in flight while the
     // multiply-adds of channel c run, so the L2 latency of the filter stream is hidden.
-    // Halo staging: lane -> (pixel, channel quarter) slots; the element offset of each slot inside
-    // one (image, channel block) plane is fixed for the whole task (-1 = outside the image).
-    constexpr int NST = (HP * 4 + 63) / 64;
-    int soff[NST];
-#pragma unroll
-    for (int jj = 0; jj < NST; ++jj) {
-        const int idx = jj * kWave + lane;
-        const int pix = idx >> 2, q = idx & 3;
-        const int ih = ih0 + pix / HW, iw = iw0 + pix % HW;
-        soff[jj] = (pix < HP && ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi) ? (ih * g.Wi + iw) * kBlk + q * 4 : -1;
-    }
+    constexpr int NST = (HP * 4 + 63) / 64;         // halo staging slots (pixel, channel quarter) per lane
 
     const int cb_begin = cpart * (CiB / CS), cb_end = cb_begin + CiB / CS;      // CiB % CS == 0
     const int c_last = cb_end * kBlk - 1;
@@ -188,14 +186,21 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
         // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----
         __builtin_amdgcn_wave_barrier();
         {
+            // The slot arithmetic is redone for every block from a lane index the compiler cannot
+            // see through: a few dozen instructions per 16 channels, instead of address registers
+            // that would stay live (and spill) across the whole reduction.
+            int sl = lane;
+            asm volatile("" : "+v"(sl));
             const float *plane = in + act_off(n, cb, 0, 0, CiB, g.Hi, g.Wi);      // wave-uniform base
 #pragma unroll
             for (int jj = 0; jj < NST; ++jj) {
-                const int idx = jj * kWave + lane;
+                const int idx = jj * kWave + sl;
                 const int pix = idx >> 2, q = idx & 3;
                 if (pix < HP) {
+                    const int ih = ih0 + pix / HW, iw = iw0 + pix % HW;
                     float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (soff[jj] >= 0) val = *reinterpret_cast<const float4 *>(plane + soff[jj]);
+                    if (ih >= 0 && ih < g.Hi && iw >= 0 && iw < g.Wi)
+                        val = *reinterpret_cast<const float4 *>(plane + (ih * g.Wi + iw) * kBlk + q * 4);
                     lds[(q * 4 + 0) * PST + pix] = val.x;
                     lds[(q * 4 + 1) * PST + pix] = val.y;
                     lds[(q * 4 + 2) * PST + pix] = val.z;
@@ -242,21 +247,25 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     }
 
     // ---- store the tile ----
+    // The lane index is passed through an empty asm so that the compiler cannot hoist the store
+    // address arithmetic above the main loop, where it would be spilled to scratch for the whole
+    // reduction (the kernel runs at the 128-register limit of 4 wavefronts per SIMD).
+    int lane_late = lane;
+    asm volatile("" : "+v"(lane_late));
     if (valid && cpart == 0) {
 #pragma unroll
         for (int j = 0; j < KPL; ++j) {
-            if (!kact[j]) continue;
-            const int k = kt * Cfg::KT + j * kWave + lane;
+            const int k = kt * Cfg::KT + j * kWave + lane_late;
+            if (k >= g.Ko) continue;
             const int kb = k / kBlk, ki = k % kBlk;
+            float *op = out + act_off(n, kb, oh0, ow0, KoB, g.Ho, g.Wo) + ki;
 #pragma unroll
             for (int a = 0; a < TH; ++a) {
-                const int oh = oh0 + a;
-                if (oh >= g.Ho) continue;
+                if (oh0 + a >= g.Ho) continue;
 #pragma unroll
                 for (int b = 0; b < TW; ++b) {
-                    const int ow = ow0 + b;
-                    if (ow >= g.Wo) continue;
-                    out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[j][a * TW + b];
+                    if (ow0 + b >= g.Wo) continue;
+                    op[(a * g.Wo + b) * kBlk] = acc[j][a * TW + b];
                 }
             }
         }
@@ -269,12 +278,14 @@ hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out,
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
     const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
     const int ktiles = ceil_div(g.Ko, Cfg::KT);
-    const long long total = (long long)tiles_w * tiles_h * ktiles * g.N;
-    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
+    const long long tiles = (long long)tiles_w * tiles_h * g.N;
     constexpr int per_wg = Cfg::WAVES / CS;
-    dim3 grid((unsigned)((total + per_wg - 1) / per_wg));
-    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS>), grid, dim3(256), 0, s, g, in, f, out,
-                       tiles_w, tiles_h, ktiles, (int)total);
+    const long long slots = (tiles + per_wg - 1) / per_wg;             // workgroups per output-channel tile
+    const long long slots_per_xcd = (slots + 7) / 8;
+    const long long blocks = slots_per_xcd * 8 * ktiles;
+    if (tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS>), dim3((unsigned)blocks), dim3(256), 0, s,
+                       g, in, f, out, tiles_w, tiles_h, ktiles, (int)tiles, (int)slots_per_xcd);
     return hipGetLastError();
 }
 
