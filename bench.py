@@ -156,6 +156,7 @@ def main():
         return torch.empty(max(n, 4) // 4, dtype=torch.float32, device=dev) if n else None
 
     ws = {(p, dn): ws_for(p, dn) for p in (0, 1, 2) for dn in (False, True)}
+    ws_dy = ws_for(st.ST_PASS_BWW_DY, False)
 
     def run_pass(name, dense, xin=None, dyin=None):
         xin = xd if xin is None else xin
@@ -164,6 +165,8 @@ def main():
             (st.st_conv_fwd_dense if dense else st.st_conv_fwd)(d, xin, wd, y, ws[0, dense], stream)
         elif name == "bwi":
             (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(d, dyin, wd, dx, ws[1, dense], stream)
+        elif name == "bww_dy":          # side measurement: BWW with the zero test on dy (not part of the step)
+            st.st_conv_bww_dy(d, xin, dyin, dw, ws_dy, stream)
         else:
             (st.st_conv_bww_dense if dense else st.st_conv_bww)(d, xin, dyin, dw, ws[2, dense], stream)
 
@@ -221,6 +224,10 @@ def main():
             "tested_zero_fraction": round(tested_p[name], 4),
         }
 
+    dy_med, _ = time_pass("bww_dy", False, args.steps)
+    passes["bww"]["tests_dy_ms"] = round(dy_med, 4)
+    passes["bww"]["tests_dy_zero_fraction"] = round(pdy, 4)
+
     # ---- roofline of the dominant kernel ----
     # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy), so the
     # event time of st_conv_fwd is that kernel's launch duration.  Algorithmic work per launch:
@@ -253,6 +260,7 @@ def main():
                 row[name] = {"sparse_ms": round(s_med, 4), "dense_ms": round(d_med, 4),
                              "speedup": round(d_med / s_med, 3),
                              "effective_tflops": round(F / (s_med * 1e-3) / 1e12, 2)}
+            row["bww"]["tests_dy_ms"] = round(time_pass("bww_dy", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
             sweep.append(row)
             del xs, dys
 

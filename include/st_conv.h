@@ -69,7 +69,7 @@ typedef struct {
     int32_t pad_w, pad_h;       /* zeros added on each side of W / of H */
 } st_conv_desc;
 
-enum { ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2 };
+enum { ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2, ST_PASS_BWW_DY = 3 };
 
 /*
  * FWD, Eq. (1) of Sec. 2.1 (correlation, filter not flipped, no bias):
@@ -117,8 +117,19 @@ st_status st_conv_bww_dense(const st_conv_desc *desc, const float *x, const floa
                             void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * BWW with the zero test on dy instead of x: Sec. 3.4 notes that Alg. 4 is easily changed to check
+ * dy when the layer's output gradient is the sparser operand, and Sec. 5.3 chooses per layer the
+ * operand with the higher average sparsity.  Same tensors, same result as st_conv_bww; all products
+ * of a dy element that is zero are skipped.  The choice is the caller's (it knows the layer's
+ * statistics); workspace size: st_conv_workspace_bytes(desc, ST_PASS_BWW_DY, 0).
+ */
+st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
+                         void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Bytes of device workspace the given pass needs for this geometry
- * (pass = ST_PASS_*, dense = 0 for st_conv_<pass>, 1 for st_conv_<pass>_dense).
+ * (pass = ST_PASS_*, dense = 0 for st_conv_<pass>, 1 for st_conv_<pass>_dense; ST_PASS_BWW_DY with
+ * dense = 0 is st_conv_bww_dy).
  * Returns 0 when none is needed or when desc is invalid (the pass itself then
  * reports the error).  The workspace must be 256-byte aligned.  Its contents
  * need not be initialised and are undefined afterwards; two calls that are in

@@ -293,6 +293,30 @@ __global__ __launch_bounds__(256) void bww_reduce_kernel(const float4 *__restric
     dw[i] = s;
 }
 
+// The same sum for the run with the operand roles swapped (BWW that tests dy): the partials hold
+// dw'[c][k][S-1-v][R-1-u] in the filter layout of a layer with C and K exchanged; this kernel adds
+// them and writes dw[k][c][v][u] in the library layout.
+__global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__restrict__ part,
+                                                                 float *__restrict__ dw, int K, int C, int S,
+                                                                 int R, int splits)
+{
+    const size_t total = (size_t)K * C * S * R;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    size_t t = i;
+    const int ki = t % kBlk; t /= kBlk;
+    const int ci = t % kBlk; t /= kBlk;
+    const int u = t % R; t /= R;
+    const int v = t % S; t /= S;
+    const int cb = t % (C / kBlk);
+    const int kb = (int)(t / (C / kBlk));
+    const size_t src = ((((size_t)cb * (K / kBlk) + kb) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) +
+                       ki * kBlk + ci;
+    float sum = part[src];
+    for (int p = 1; p < splits; ++p) sum += part[(size_t)p * total + src];
+    dw[i] = sum;
+}
+
 constexpr int kSparseTH = 8, kSparseTW = 8;
 constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
 
@@ -370,6 +394,53 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
+}
+
+// BWW that tests dy: the same kernel with the operand roles exchanged.  With unit stride,
+//   dw[k,c,v,u] = sum x[n,c,oh-ph+v,ow-pw+u] dy[n,k,oh,ow] = sum dy[n,k,ih-ph'+v',iw-pw'+u'] x[n,c,ih,iw]
+// for v' = S-1-v, ph' = S-1-ph (same for the width), i.e. the filter gradient of a layer whose
+// input is dy (K channels, OH x OW, padding S-1-pad) and whose output gradient is x (C channels).
+namespace {
+st_conv_desc swapped_desc(const st_conv_desc &d)
+{
+    st_conv_desc e = d;
+    e.C = d.K; e.K = d.C;
+    e.H = d.H + 2 * d.pad_h - d.S + 1;
+    e.W = d.W + 2 * d.pad_w - d.R + 1;
+    e.pad_h = d.S - 1 - d.pad_h;
+    e.pad_w = d.R - 1 - d.pad_w;
+    return e;
+}
+}  // namespace
+
+bool bww_dy_fast_supported(const st_conv_desc &d)
+{
+    return bww_fast_supported(d) && d.pad_h <= d.S - 1 && d.pad_w <= d.R - 1 && bww_fast_supported(swapped_desc(d));
+}
+
+size_t bww_sparse_dy_workspace(const st_conv_desc &d)
+{
+    const st_conv_desc e = swapped_desc(d);
+    const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
+    return (size_t)A.splits * d.K * d.C * d.S * d.R * sizeof(float);        // always staged, even for one split
+}
+
+hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                                float *ws, hipStream_t s)
+{
+    const st_conv_desc e = swapped_desc(d);
+    const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
+    dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
+    if (d.R == 3)
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
+    else
+        hipLaunchKernelGGL((bww_sparse_kernel<1, 1, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const size_t total = (size_t)d.K * d.C * d.S * d.R;
+    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ws, dw,
+                       d.K, d.C, d.S, d.R, A.splits);
+    return hipGetLastError();
 }
 
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,

@@ -36,6 +36,8 @@ hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const floa
                               bool sparse, hipStream_t s);
 hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                               bool sparse, hipStream_t s);
+hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                                 hipStream_t s);
 
 // filter transposition for stride-1 BWI: wt[C/16][K/16][S][R][16 k][16 c] with taps reversed
 hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s);
@@ -54,6 +56,11 @@ bool bww_fast_supported(const st_conv_desc &d);
 size_t bww_sparse_workspace(const st_conv_desc &d);
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                              float *ws, hipStream_t s);
+// BWW that tests dy instead of x (operand roles exchanged, transposing final sum)
+bool bww_dy_fast_supported(const st_conv_desc &d);
+size_t bww_sparse_dy_workspace(const st_conv_desc &d);
+hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                                float *ws, hipStream_t s);
 size_t bww_dense_workspace(const st_conv_desc &d);
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                             float *ws, hipStream_t s);

@@ -81,6 +81,9 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
     case ST_PASS_BWW:
         if (!st::bww_fast_supported(d)) return 0;
         return dense ? st::bww_dense_workspace(d) : st::bww_sparse_workspace(d);
+    case ST_PASS_BWW_DY:
+        if (dense) return workspace_bytes(d, o, ST_PASS_BWW, true);
+        return st::bww_dy_fast_supported(d) ? st::bww_sparse_dy_workspace(d) : 0;
     default:
         return 0;
     }
@@ -145,6 +148,20 @@ st_status run_bww(const st_conv_desc *d, const float *x, const float *dy, float 
                      : st::launch_bww_sparse(*d, x, dy, dw, wsf, s));
 }
 
+st_status run_bww_dy(const st_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
+                     size_t ws_bytes, void *stream)
+{
+    Dims o;
+    st_status rc = validate(d, &o);
+    if (rc != ST_OK) return rc;
+    if (!x || !dy || !dw) return ST_ERR_NULL;
+    if ((long long)d->K * d->S * d->R > 0x7fffffffLL) return ST_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!st::bww_dy_fast_supported(*d)) return dev(st::launch_generic_bww_dy(*d, x, dy, dw, s));
+    if (!ws_ok(ws, ws_bytes, st::bww_sparse_dy_workspace(*d))) return ST_ERR_WORKSPACE;
+    return dev(st::launch_bww_sparse_dy(*d, x, dy, dw, static_cast<float *>(ws), s));
+}
+
 }  // namespace
 
 extern "C" {
@@ -179,6 +196,12 @@ st_status st_conv_bww(const st_conv_desc *desc, const float *x, const float *dy,
     return run_bww(desc, x, dy, dw, ws, ws_bytes, hip_stream, false);
 }
 
+st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *dy, float *dw, void *ws,
+                         size_t ws_bytes, void *hip_stream)
+{
+    return run_bww_dy(desc, x, dy, dw, ws, ws_bytes, hip_stream);
+}
+
 st_status st_conv_bww_dense(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
                             void *ws, size_t ws_bytes, void *hip_stream)
 {
@@ -205,6 +228,6 @@ const char *st_status_str(st_status status)
     }
 }
 
-const char *st_conv_version(void) { return "0.1"; }
+const char *st_conv_version(void) { return "0.2"; }
 
 }  // extern "C"

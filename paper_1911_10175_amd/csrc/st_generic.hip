@@ -127,6 +127,38 @@ __global__ __launch_bounds__(64) void generic_bww_kernel(st_conv_desc d, int OH,
     if (active) dw[flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk + ki] = acc;
 }
 
+// dw[k,c,v,u] for c = 64*blockIdx.y + lane, (k,v,u) from blockIdx.x; the tested operand is dy
+__global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int OH, int OW,
+                                                            const float *__restrict__ x,
+                                                            const float *__restrict__ dy,
+                                                            float *__restrict__ dw)
+{
+    const int lane = threadIdx.x;
+    const int c = blockIdx.y * kWave + lane;
+    int t = blockIdx.x;
+    const int u = t % d.R; t /= d.R;
+    const int v = t % d.S; t /= d.S;
+    const int k = t;
+    const int CB = d.C / kBlk, KB = d.K / kBlk;
+    const bool active = c < d.C;
+    const int cb = active ? c / kBlk : 0, ci = c % kBlk;
+    const int kb = k / kBlk, ki = k % kBlk;
+    float acc = 0.f;
+    for (int n = 0; n < d.N; ++n)
+        for (int oh = 0; oh < OH; ++oh) {
+            const int ih = oh * d.stride_h - d.pad_h + v;
+            if (ih < 0 || ih >= d.H) continue;
+            for (int ow = 0; ow < OW; ++ow) {
+                const int iw = ow * d.stride_w - d.pad_w + u;
+                if (iw < 0 || iw >= d.W) continue;
+                const float gv = dy[act_off(n, kb, oh, ow, KB, OH, OW) + ki];     // same address in every lane
+                if (!(gv != 0.f)) continue;
+                acc = fmaf(x[act_off(n, cb, ih, iw, CB, d.H, d.W) + ci], gv, acc);
+            }
+        }
+    if (active) dw[flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk + ki] = acc;
+}
+
 // wt[cb][kb][S-1-v][R-1-u][ki][ci] = w[kb][cb][v][u][ci][ki]
 __global__ __launch_bounds__(256) void transpose_filters_kernel(int KB, int CB, int S, int R,
                                                                 const float *__restrict__ w,
@@ -189,6 +221,16 @@ hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float
         hipLaunchKernelGGL(generic_bww_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
     else
         hipLaunchKernelGGL(generic_bww_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
+    return hipGetLastError();
+}
+
+hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
+                                 hipStream_t s)
+{
+    int OH, OW;
+    out_dims(d, OH, OW);
+    dim3 grid(d.K * d.S * d.R, ceil_div(d.C, kWave), 1);
+    hipLaunchKernelGGL(generic_bww_dy_kernel, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
     return hipGetLastError();
 }
 

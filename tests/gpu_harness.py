@@ -60,12 +60,22 @@ class DeviceLayer:
         return st.unpack_activations(dx.cpu().numpy())
 
     def bww(self, dense=False):
+        """dense = False: st_conv_bww (tests x); True: st_conv_bww_dense; "dy": st_conv_bww_dy."""
         g = self.g
         dw = nan_like((g.K // 16, g.C // 16, g.S, g.R, 16, 16))
-        ws = workspace(self.d, st.ST_PASS_BWW, dense)
-        (st.st_conv_bww_dense if dense else st.st_conv_bww)(self.d, self.x, self.dy, dw, ws)
+        if dense == "dy":
+            ws = workspace(self.d, st.ST_PASS_BWW_DY, False)
+            st.st_conv_bww_dy(self.d, self.x, self.dy, dw, ws)
+        else:
+            ws = workspace(self.d, st.ST_PASS_BWW, dense)
+            (st.st_conv_bww_dense if dense else st.st_conv_bww)(self.d, self.x, self.dy, dw, ws)
         torch.cuda.synchronize()
         return st.unpack_filters(dw.cpu().numpy())
+
+
+def bww_variants(variants):
+    """The BWW entry points to check: the dy-testing one rides along with the x-testing one."""
+    return tuple(variants) + (("dy",) if False in variants else ())
 
 
 def assert_close(got, ref, ref_abs, what):
@@ -91,7 +101,7 @@ def check_all_passes_full(g: Geom, x, w, dy, label, passes=("fwd", "bwi", "bww")
             errs["bwi", dense] = assert_close(L.bwi(dense), ref, ref_abs, f"{label} BWI dense={dense}")
     if "bww" in passes:
         ref, ref_abs = st_ref.conv_bww(g, x, dy)
-        for dense in variants:
+        for dense in bww_variants(variants):
             errs["bww", dense] = assert_close(L.bww(dense), ref, ref_abs, f"{label} BWW dense={dense}")
     return errs
 
@@ -124,7 +134,7 @@ def check_all_passes_sampled(g: Geom, x, w, dy, label, n_samples=4096, seed=0, v
         assert_close(got[tuple(cx.T)], ref, ref_abs, f"{label} BWI dense={dense} (sampled)")
     cw = sample_coords(g.w_shape, n_bww, seed + 2)
     ref, ref_abs = st_ref.conv_bww_at(g, x, dy, cw)
-    for dense in variants:
+    for dense in bww_variants(variants):
         got = L.bww(dense)
         assert np.isfinite(got).all()
         assert_close(got[tuple(cw.T)], ref, ref_abs, f"{label} BWW dense={dense} (sampled)")

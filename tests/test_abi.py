@@ -44,12 +44,13 @@ def test_validation_happens_on_the_host():
     assert st.st_conv_fwd(good, None, None, None, check=False) == 1
     assert st.st_conv_bwi_dense(good, None, None, None, check=False) == 1
     assert st.st_conv_bww(good, None, None, None, check=False) == 1
+    assert st.st_conv_bww_dy(good, None, None, None, check=False) == 1
     bad = [st.ConvDesc(0, 16, 16, 8, 8, 3, 3), st.ConvDesc(1, 8, 16, 8, 8, 3, 3, 1, 1, 1, 1),
            st.ConvDesc(1, 16, 24, 8, 8, 3, 3, 1, 1, 1, 1), st.ConvDesc(1, 16, 16, 2, 8, 3, 3),
            st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 0, 1), st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 1, 1, -1, 0)]
     for d in bad:
         for fn in (st.st_conv_fwd, st.st_conv_fwd_dense, st.st_conv_bwi, st.st_conv_bwi_dense,
-                   st.st_conv_bww, st.st_conv_bww_dense):
+                   st.st_conv_bww, st.st_conv_bww_dense, st.st_conv_bww_dy):
             assert fn(d, 256, 256, 256, check=False) == 2, d
         assert st.st_conv_workspace_bytes(d, st.ST_PASS_BWI) == 0
     with pytest.raises(st.StConvError) as e:
@@ -73,6 +74,14 @@ def test_workspace_query_and_rejection():
             fn = st.st_conv_bww_dense if dense else st.st_conv_bww
             assert fn(d, 256, 256, 256, ws=None, check=False) == 4
             assert fn(d, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
+    # the dy-testing BWW always stages its partial sums, even a single one
+    for dd in (d, st.ConvDesc(1, 512, 512, 8, 8, 3, 3, 1, 1, 1, 1)):
+        need = st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW_DY)
+        assert need >= dd.K * dd.C * 9 * 4 and need % (dd.K * dd.C * 9 * 4) == 0
+        assert st.st_conv_bww_dy(dd, 256, 256, 256, ws=None, check=False) == 4
+        assert st.st_conv_bww_dy(dd, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
+    # shapes served by the generic kernel need none
+    assert st.st_conv_workspace_bytes(st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 2, 2, 1, 1), st.ST_PASS_BWW_DY) == 0
     assert st.st_conv_workspace_bytes(d, 7) == 0
 
 

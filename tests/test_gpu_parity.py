@@ -117,6 +117,44 @@ def test_sparse_equals_dense_control_and_is_deterministic():
         assert np.allclose(a, c, rtol=1e-3, atol=1e-4)
 
 
+BWW_DY_SHAPES = [
+    ("3x3 pad0 C<K", Geom(2, 32, 80, 13, 19, 3, 3, 1, 1, 0, 0)),
+    ("3x3 pad2 C>K", Geom(2, 144, 48, 9, 12, 3, 3, 1, 1, 2, 2)),
+    ("3x3 pad(1,0)", Geom(3, 64, 64, 17, 8, 3, 3, 1, 1, 1, 0)),
+    ("1x1", Geom(2, 96, 208, 14, 14, 1, 1, 1, 1, 0, 0)),
+    ("3x3 stride2 (generic)", Geom(2, 32, 48, 15, 15, 3, 3, 2, 2, 1, 1)),
+    ("5x5 (generic)", Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2)),
+]
+
+
+@pytest.mark.parametrize("label,g", BWW_DY_SHAPES, ids=[s[0] for s in BWW_DY_SHAPES])
+@pytest.mark.parametrize("px,pdy", [(0.0, 0.9), (0.6, 0.5)])
+def test_bww_dy_tested_operand(label, g, px, pdy):
+    """BWW with the zero test on dy (Sec. 3.4, closing remark): same tensor as the x-testing form."""
+    x, w, dy = synth(g, px, pdy, seed=31)
+    L = DeviceLayer(g, x, w, dy)
+    ref, ref_abs = st_ref.conv_bww(g, x, dy)
+    got = L.bww("dy")
+    assert_close(got, ref, ref_abs, f"{label} BWW tests dy")
+    assert np.array_equal(got, L.bww("dy")), "two runs differ"
+
+
+def test_bww_dy_skips_on_dy_only():
+    """All-zero dy with non-finite-free x gives exactly zero; -0 in dy is skipped, a denormal is kept."""
+    g = Geom(1, 16, 16, 8, 8, 3, 3, 1, 1, 1, 1)
+    x = np.full(g.x_shape, 1e30, np.float32)
+    dy = np.zeros(g.y_shape, np.float32)
+    dy[0, :, ::2, ::2] = -0.0
+    L = DeviceLayer(g, x, None, dy)
+    assert not L.bww("dy").any()
+    dy[0, 7, 5, 2] = 1e-40
+    L = DeviceLayer(g, x, None, dy)
+    ref, ref_abs = st_ref.conv_bww(g, x, dy)
+    got = L.bww("dy")
+    assert_close(got, ref, ref_abs, "denormal dy")
+    assert got[7, 0, 1, 1] > 0
+
+
 def test_config3_resnet3_2_full():
     """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
     L = stgen.RESNET3_2
