@@ -275,7 +275,11 @@ hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w
 hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
     if (g.R == 3 && g.S == 3) return launch_rs<3, 3>(g, in, wd, out, s);
-    if (g.R == 1 && g.S == 1) return launch_rs<1, 1>(g, in, wd, out, s);
+    if (g.R == 1 && g.S == 1) {
+        // minibatch-wide pixel numbering of the pointwise kernel is kept in int
+        if ((long long)g.N * g.Ho * g.Wo <= 0x7fffff00LL) return launch_pw_dense(g, in, wd, out, s);
+        return launch_rs<1, 1>(g, in, wd, out, s);
+    }
     return hipErrorInvalidValue;
 }
 

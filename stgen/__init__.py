@@ -164,6 +164,24 @@ def vgg16_stack(p: float, n: int = 32):
     return [Layer(nm, n, c, k, hw, hw, 3, 3, 1, p, p) for nm, c, k, hw in spec]
 
 
+def table1_layers(n: int = 32, p_x: float = 0.5, p_dy: float = 0.5):
+    """Every row of the paper's Table 1 (VGG16 and ResNet-50 v1.5 layer shapes), padding (R-1)/2."""
+    spec = [("vgg1_2", 64, 64, 224, 3, 1), ("vgg2_1", 64, 128, 112, 3, 1), ("vgg2_2", 128, 128, 112, 3, 1),
+            ("vgg3_1", 128, 256, 56, 3, 1), ("vgg3_2", 256, 256, 56, 3, 1), ("vgg4_1", 256, 512, 28, 3, 1),
+            ("vgg4_2", 512, 512, 28, 3, 1), ("vgg5_1", 512, 512, 14, 3, 1), ("resnet2_1a", 64, 64, 56, 1, 1),
+            ("resnet2_1b", 256, 64, 56, 1, 1), ("resnet2_2", 64, 64, 56, 3, 1), ("resnet2_3", 64, 256, 56, 1, 1),
+            ("resnet3_1a", 256, 128, 56, 1, 1), ("resnet3_1b", 512, 128, 28, 1, 1),
+            ("resnet3_2", 128, 128, 28, 3, 1), ("resnet3_2/r", 128, 128, 56, 3, 2),
+            ("resnet3_3", 128, 512, 28, 1, 1), ("resnet4_1a", 512, 256, 28, 1, 1),
+            ("resnet4_1b", 1024, 256, 14, 1, 1), ("resnet4_2", 256, 256, 14, 3, 1),
+            ("resnet4_2/r", 256, 256, 28, 3, 2), ("resnet4_3", 256, 1024, 14, 1, 1),
+            ("resnet5_1a", 1024, 512, 14, 1, 1), ("resnet5_1b", 2048, 512, 7, 1, 1),
+            ("resnet5_2", 512, 512, 7, 3, 1), ("resnet5_2/r", 512, 512, 14, 3, 2),
+            ("resnet5_3", 512, 2048, 7, 1, 1)]
+    return [Layer(nm, n, c, k, hw, hw, r, r, (r - 1) // 2, p_x, p_dy, stride)
+            for nm, c, k, hw, r, stride in spec]
+
+
 def make_layer_tensors(layer: Layer, seed: int = 0):
     """(x, w, dy) for a layer in plain layouts, fp32.
 
