@@ -24,6 +24,8 @@ struct Geom {
     int R, S;            // filter width, height
     int sw, sh;          // strides
     int pw, ph;          // padding
+    int uw, uh;          // spacing of the input samples on the grid the taps slide over (1; 2 for the
+                         // BWI of a stride-2 layer, whose dy is spread out with zeros in between)
 };
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

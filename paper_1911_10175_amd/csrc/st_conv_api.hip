@@ -35,19 +35,21 @@ Geom fwd_geom(const st_conv_desc &d, const Dims &o)
     g.N = d.N; g.Ci = d.C; g.Ko = d.K;
     g.Hi = d.H; g.Wi = d.W; g.Ho = o.OH; g.Wo = o.OW;
     g.R = d.R; g.S = d.S; g.sw = d.stride_w; g.sh = d.stride_h; g.pw = d.pad_w; g.ph = d.pad_h;
+    g.uw = 1; g.uh = 1;
     return g;
 }
 
-// Unit-stride BWI as a correlation of dy with transposed, tap-reversed filters
-// (SparseTrain Sec. 3.3): input = dy [N][K][OH][OW], output = dx [N][C][H][W],
-// padding S-1-pad_h / R-1-pad_w.
+// BWI as a correlation of dy with transposed, tap-reversed filters (SparseTrain Sec. 3.3):
+// input = dy [N][K][OH][OW], output = dx [N][C][H][W], padding S-1-pad_h / R-1-pad_w.  With a
+// stride the dy samples sit stride positions apart on the grid the taps slide over
+// (dx[ih] = sum_v' dyU[ih - (S-1-pad_h) + v'] w[S-1-v'] with dyU[stride*oh] = dy[oh], 0 elsewhere).
 bool bwi_as_fwd(const st_conv_desc &d, const Dims &o, Geom *g)
 {
-    if (d.stride_w != 1 || d.stride_h != 1) return false;
     if (d.pad_w > d.R - 1 || d.pad_h > d.S - 1) return false;
     g->N = d.N; g->Ci = d.K; g->Ko = d.C;
     g->Hi = o.OH; g->Wi = o.OW; g->Ho = d.H; g->Wo = d.W;
     g->R = d.R; g->S = d.S; g->sw = 1; g->sh = 1;
+    g->uw = d.stride_w; g->uh = d.stride_h;
     g->pw = d.R - 1 - d.pad_w; g->ph = d.S - 1 - d.pad_h;
     return true;
 }

@@ -252,7 +252,7 @@ hipError_t launch_rs(const Geom &g, const float *in, const float *wd, float *out
 
 bool fwd_dense_supported(const Geom &g)
 {
-    if (g.sw != 1 || g.sh != 1) return false;
+    if (g.sw != 1 || g.sh != 1 || g.uw != 1 || g.uh != 1) return false;
     if (g.R == 3 && g.S == 3) return g.pw <= 2 && g.ph <= 2;
     if (g.R == 1 && g.S == 1) return g.pw == 0 && g.ph == 0;
     return false;

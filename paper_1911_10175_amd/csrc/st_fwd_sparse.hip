@@ -36,9 +36,19 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-template <int R, int S, int TH, int TW, int KPL>
+// SD = stride of the correlation (the output samples every SD-th position), SU = spacing of the
+// input samples (SU = 2: the input sits on every second position of the grid the taps slide over,
+// which is how the BWI of a stride-2 layer looks: Sec. 3.3 of the paper, dX receives O*P times
+// more updates per dY element).  With p(a) = a*SU + OFF the grid position of halo pixel a relative
+// to the first position the tile's taps reach, tap v of output row ol reads position ol*SD + v, so
+// halo pixel a feeds output row (p(a) - v) / SD for every v that makes this an integer in range.
+template <int R, int S, int TH, int TW, int KPL, int SD = 1, int SU = 1, int OFF = 0>
 struct FwdSparseCfg {
-    static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
+    static_assert(SD == 1 || SU == 1, "strided and dilated at once is not needed");
+    static_assert(OFF < SU, "offset of the first input sample within its spacing");
+    static constexpr int HH = ((TH - 1) * SD + S - 1 - OFF) / SU + 1;
+    static constexpr int HW = ((TW - 1) * SD + R - 1 - OFF) / SU + 1;
+    static constexpr int HP = HH * HW;
     static constexpr int NXV = (HP + 63) / 64;              // registers holding one channel of the halo
     static constexpr int PST = ((HP + 7) / 8) * 8 + 4;      // LDS pixel stride, = 4 (mod 8), >= HP rounded up to 4
     static constexpr int WAVES = 4;
@@ -48,14 +58,14 @@ struct FwdSparseCfg {
 // CS = number of wavefronts that share one task, each reducing 1/CS of the input channels; their
 // partial tiles are added through LDS at the end (in a fixed order).  CS > 1 multiplies the
 // number of wavefronts of a layer with few tiles without shrinking the tile.
-template <int R, int S, int TH, int TW, int KPL, int MINW, int CS>
+template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD = 1, int SU = 1, int OFF = 0>
 __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
                                                          const float *__restrict__ f,
                                                          float *__restrict__ out,
                                                          int tiles_w, int tiles_h, int ktiles, int total,
                                                                int slots_per_xcd)
 {
-    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
     __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][kBlk * PST];
 
@@ -78,7 +88,9 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     const int th = t % tiles_h;
     const int n = t / tiles_h;
     const int oh0 = th * TH, ow0 = tw * TW;
-    const int ih0 = oh0 - g.ph, iw0 = ow0 - g.pw;
+    // first input sample of the halo; with SU = 2 the host guarantees that the division is exact
+    // (even tile sizes, padding of the same parity as OFF)
+    const int ih0 = (oh0 * SD - g.ph + OFF) / SU, iw0 = (ow0 * SD - g.pw + OFF) / SU;
     const int CiB = g.Ci / kBlk, KoB = g.Ko / kBlk;
 
     float acc[KPL][TH * TW];
@@ -146,17 +158,17 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
             static_for<0, 4>([&](auto J) __attribute__((always_inline)) {
                 constexpr int i = gidx * 4 + decltype(J)::value;
                 if constexpr (i < HP) {
-                    constexpr int a = i / HW, b = i % HW;
+                    constexpr int a = (i / HW) * SU + OFF, b = (i % HW) * SU + OFF;    // grid position
                     if (__builtin_expect((m32[i / 32] & (1u << (i % 32))) != 0u, 1)) {
                         const float xs = xg[i % 4];
 #pragma unroll
                         for (int v = 0; v < S; ++v) {
-                            const int ol = a - v;
-                            if (ol < 0 || ol >= TH) continue;
+                            if (a - v < 0 || (a - v) % SD != 0 || (a - v) / SD >= TH) continue;
+                            const int ol = (a - v) / SD;
 #pragma unroll
                             for (int u = 0; u < R; ++u) {
-                                const int oc = b - u;
-                                if (oc < 0 || oc >= TW) continue;
+                                if (b - u < 0 || (b - u) % SD != 0 || (b - u) / SD >= TW) continue;
+                                const int oc = (b - u) / SD;
 #pragma unroll
                                 for (int j = 0; j < KPL; ++j)
                                     acc[j][ol * TW + oc] = fmaf(xs, wv[j][v * R + u], acc[j][ol * TW + oc]);
@@ -272,10 +284,10 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     }
 }
 
-template <int R, int S, int TH, int TW, int KPL, int MINW, int CS>
+template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD, int SU, int OFF>
 hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
-    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
     const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
     const int ktiles = ceil_div(g.Ko, Cfg::KT);
     const long long tiles = (long long)tiles_w * tiles_h * g.N;
@@ -284,7 +296,7 @@ hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out,
     const long long slots_per_xcd = (slots + 7) / 8;
     const long long blocks = slots_per_xcd * 8 * ktiles;
     if (tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS>), dim3((unsigned)blocks), dim3(256), 0, s,
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS, SD, SU, OFF>), dim3((unsigned)blocks), dim3(256), 0, s,
                        g, in, f, out, tiles_w, tiles_h, ktiles, (int)tiles, (int)slots_per_xcd);
     return hipGetLastError();
 }
@@ -292,10 +304,10 @@ hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out,
 // Picks the channel split: layers with few tiles get 2 or 4 wavefronts per task so that the chip
 // (1024 SIMDs x 4 resident wavefronts) is filled and the tail is short.  ST_FWD_SPARSE_CS
 // overrides (tuning aid).
-template <int R, int S, int TH, int TW, int KPL, int MINW>
+template <int R, int S, int TH, int TW, int KPL, int MINW, int SD = 1, int SU = 1, int OFF = 0>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
-    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL>;
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
     const long long tasks = (long long)ceil_div(g.Wo, TW) * ceil_div(g.Ho, TH) * ceil_div(g.Ko, Cfg::KT) * g.N;
     const int CiB = g.Ci / kBlk;
     int cs = 1;
@@ -306,16 +318,21 @@ hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out
         const int e = atoi(env);
         if ((e == 1 || e == 2 || e == 4) && CiB % e == 0) cs = e;
     }
-    if (cs == 4) return launch_cs<R, S, TH, TW, KPL, MINW, 4>(g, in, f, out, s);
-    if (cs == 2) return launch_cs<R, S, TH, TW, KPL, MINW, 2>(g, in, f, out, s);
-    return launch_cs<R, S, TH, TW, KPL, MINW, 1>(g, in, f, out, s);
+    if (cs == 4) return launch_cs<R, S, TH, TW, KPL, MINW, 4, SD, SU, OFF>(g, in, f, out, s);
+    if (cs == 2) return launch_cs<R, S, TH, TW, KPL, MINW, 2, SD, SU, OFF>(g, in, f, out, s);
+    return launch_cs<R, S, TH, TW, KPL, MINW, 1, SD, SU, OFF>(g, in, f, out, s);
 }
 
 }  // namespace
 
 bool fwd_sparse_supported(const Geom &g)
 {
-    if (g.sw != 1 || g.sh != 1) return false;
+    if (g.sw != g.sh || g.uw != g.uh) return false;
+    if (g.sw == 2 && g.uw == 1)                     // stride-2 3x3 layers (FWD)
+        return g.R == 3 && g.S == 3 && g.pw <= 2 && g.ph <= 2;
+    if (g.sw == 1 && g.uw == 2)                     // their BWI: input samples on every second position
+        return g.R == 3 && g.S == 3 && g.pw == 1 && g.ph == 1;
+    if (g.sw != 1 || g.uw != 1) return false;
     if (g.R == 3 && g.S == 3) return g.pw <= 2 && g.ph <= 2;
     if (g.R == 1 && g.S == 1) return g.pw == 0 && g.ph == 0;
     return false;
@@ -326,6 +343,19 @@ hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, flo
     // 64 accumulators per lane (4x8 pixels x 2 channels, or 8x8 pixels x 1 channel) keep the
     // kernel within 128 registers, i.e. 4 wavefronts per SIMD.
     const bool wide = g.Ko % 128 == 0;
+    if (g.sw == 2) {
+        // stride 2: a 4x8 output tile is fed by a 9x17 input halo, 2.25 taps per tested element on average
+        const bool seven = g.Wo % 8 != 0 && g.Wo % 7 == 0;
+        if (wide) return seven ? launch_cfg<3, 3, 4, 7, 2, 4, 2, 1, 0>(g, in, f, out, s) : launch_cfg<3, 3, 4, 8, 2, 4, 2, 1, 0>(g, in, f, out, s);
+        return seven ? launch_cfg<3, 3, 4, 7, 1, 4, 2, 1, 0>(g, in, f, out, s) : launch_cfg<3, 3, 4, 8, 1, 4, 2, 1, 0>(g, in, f, out, s);
+    }
+    if (g.uw == 2) {
+        // BWI of a stride-2 layer: every tested element feeds all 9 taps; tiles have even sides so
+        // that the position of the input samples within a tile is the same for every tile
+        const bool fourteen = g.Wo % 8 != 0 && g.Wo % 14 == 0;
+        if (wide) return fourteen ? launch_cfg<3, 3, 2, 14, 2, 4, 1, 2, 1>(g, in, f, out, s) : launch_cfg<3, 3, 4, 8, 2, 4, 1, 2, 1>(g, in, f, out, s);
+        return fourteen ? launch_cfg<3, 3, 4, 14, 1, 4, 1, 2, 1>(g, in, f, out, s) : launch_cfg<3, 3, 8, 8, 1, 4, 1, 2, 1>(g, in, f, out, s);
+    }
     if (g.R == 3 && g.S == 3) {
         // 7-wide tiles when the row length is a multiple of 7 but not of 8 (28, 14): no ragged tiles
         const bool seven = g.Wo % 8 != 0 && g.Wo % 7 == 0;

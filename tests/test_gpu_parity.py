@@ -155,6 +155,35 @@ def test_bww_dy_skips_on_dy_only():
     assert got[7, 0, 1, 1] > 0
 
 
+STRIDE2 = [
+    ("s2 32->128 @32", Geom(2, 32, 128, 32, 32, 3, 3, 2, 2, 1, 1)),          # FWD wide 4x8; BWI narrow 8x8
+    ("s2 128->48 @28", Geom(2, 128, 48, 28, 28, 3, 3, 2, 2, 1, 1)),          # FWD narrow 4x7; BWI wide 2x14
+    ("s2 128->128 30x26", Geom(1, 128, 128, 30, 26, 3, 3, 2, 2, 1, 1)),      # ragged tiles everywhere
+    ("s2 48->32 @14", Geom(2, 48, 32, 14, 14, 3, 3, 2, 2, 1, 1)),            # FWD narrow 4x7; BWI narrow 4x14
+    ("s2 64->64 15x17", Geom(1, 64, 64, 15, 17, 3, 3, 2, 2, 1, 1)),          # odd image sizes
+    ("s2 pad0", Geom(2, 32, 32, 17, 17, 3, 3, 2, 2, 0, 0)),                  # FWD tiled, BWI generic
+    ("s2 pad2", Geom(1, 16, 128, 12, 20, 3, 3, 2, 2, 2, 2)),
+    ("s2 256->256 @28", Geom(2, 256, 256, 28, 28, 3, 3, 2, 2, 1, 1)),        # Table 1 resnet4_2/r, channel split 4
+]
+
+
+@pytest.mark.parametrize("label,g", STRIDE2, ids=[s[0] for s in STRIDE2])
+def test_stride2_layers(label, g):
+    """Stride-2 3x3 layers (Table 1, the /r rows; Sec. 3.3 on BWI with a stride)."""
+    x, w, dy = synth(g, 0.5, 0.6, seed=41)
+    check_all_passes_full(g, x, w, dy, label)
+
+
+def test_stride2_degenerate_sparsity():
+    g = Geom(1, 64, 128, 16, 16, 3, 3, 2, 2, 1, 1)
+    for p in (0.0, 1.0):
+        x, w, dy = synth(g, p, p, seed=43)
+        if p == 1.0:
+            x[:] = 0.0
+            dy[:] = 0.0
+        check_all_passes_full(g, x, w, dy, f"s2 p={p}")
+
+
 def test_config3_resnet3_2_full():
     """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
     L = stgen.RESNET3_2
