@@ -43,9 +43,39 @@ struct BwwArgs {
     int cgroups;               // ceil(C/64)
 };
 
-template <int R, int S, int TH, int TW>
+// PSTEP = stride of the layer (1 or 2): positions of the halo between neighbouring tile pixels
+template <int R, int S, int TH, int TW, int PSTEP = 1>
 struct BwwCfg {
-    static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
+    static constexpr int HH = (TH - 1) * PSTEP + S, HW = (TW - 1) * PSTEP + R, HP = HH * HW;
+};
+
+// How the pixels of the tested tile, the taps and the pixels of the other operand's halo relate in
+// the zero-skipping kernel.  A group is GP = 4 consecutive tested pixels of row a starting at
+// column b0; its multiply-adds read a window of the halo that is loaded into registers once.
+//   MODE 0  unit stride: pixel j, tap (v,u) <-> window [S-1-v][j+R-1-u]  (window S x (GP+R-1) at (a, b0))
+//   MODE 1  stride 2, padding 1, x tested: x pixel (a, b0+j) meets dy row (a+1-v)/2 for the v that make
+//           this an integer, the same along the width (window 2 x 3 at (a/2, b0/2); 1, 2 or 4 taps)
+//   MODE 2  stride 2, dy tested (operands exchanged by the caller): dy pixel (a, b0+j) meets x pixel
+//           (2a+v, 2(b0+j)+u) of its halo for all taps (window 3 x 9 at (2a, 2*b0)); the partial sums
+//           are stored with the taps reversed, which is what the exchanged-roles reduction expects
+template <int R, int S, int TH, int TW, int MODE>
+struct BwwSparseCfg {
+    static constexpr int GP = 4;
+    static constexpr int HH = MODE == 0 ? TH + S - 1 : MODE == 1 ? TH / 2 + 1 : 2 * (TH - 1) + S;
+    static constexpr int HW = MODE == 0 ? TW + R - 1 : MODE == 1 ? TW / 2 + 1 : 2 * (TW - 1) + R;
+    static constexpr int HP = HH * HW;
+    static constexpr int WR = MODE == 1 ? 2 : S;
+    static constexpr int WC = MODE == 0 ? GP + R - 1 : MODE == 1 ? GP / 2 + 1 : 2 * (GP - 1) + R;
+    static constexpr int RU = MODE == 1 ? 2 : 1;            // rows whose code differs (row parity)
+    static constexpr int wrow0(int a) { return MODE == 0 ? a : MODE == 1 ? a / 2 : 2 * a; }
+    static constexpr int wcol0(int b0) { return MODE == 0 ? b0 : MODE == 1 ? b0 / 2 : 2 * b0; }
+    static constexpr bool valid(int par, int j, int v, int u)
+    {
+        return MODE != 1 || (((par + 1 - v) % 2 == 0) && ((j + 1 - u) % 2 == 0));
+    }
+    static constexpr int wr(int par, int v) { return MODE == 0 ? S - 1 - v : MODE == 1 ? (par + 1 - v) / 2 : v; }
+    static constexpr int wc(int j, int u) { return MODE == 0 ? j + R - 1 - u : MODE == 1 ? (j + 1 - u) / 2 : 2 * j + u; }
+    static constexpr int slot(int v, int u) { return MODE == 2 ? (S - 1 - v) * R + (R - 1 - u) : v * R + u; }
 };
 
 // ------------------------------------------------------------------------------------------
@@ -61,17 +91,18 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-template <int R, int S, int TH, int TW>
+template <int R, int S, int TH, int TW, int MODE = 0>
 __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
                                                             const float *__restrict__ dy,
                                                             float *__restrict__ part)
 {
-    using Cfg = BwwCfg<R, S, TH, TW>;
+    using Cfg = BwwSparseCfg<R, S, TH, TW, MODE>;
     constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
     constexpr int CH = 8;                 // input channels per wavefront
-    constexpr int GP = 4;                 // pixels per group
+    constexpr int GP = Cfg::GP;           // pixels per group
     static_assert(TW % GP == 0, "groups must not straddle rows");
-    constexpr int WC = GP + R - 1;        // dy window columns of a group
+    static_assert(TH % Cfg::RU == 0, "row parities come in pairs");
+    constexpr int WR = Cfg::WR, WC = Cfg::WC;        // dy window of a group
     __shared__ __attribute__((aligned(16))) float dyT[HP * 64];
     __shared__ __attribute__((aligned(16))) float xT[TP * 64];
 
@@ -103,7 +134,9 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
         const int th = t % A.tiles_h;
         const int n = t / A.tiles_h;
         const int ih0 = th * TH, iw0 = tw * TW;
-        const int ohs = ih0 + A.ph - (S - 1), ows = iw0 + A.pw - (R - 1);
+        // first halo pixel of the other operand (MODE 1 assumes padding 1 and even tile origins)
+        const int ohs = MODE == 0 ? ih0 + A.ph - (S - 1) : MODE == 1 ? ih0 / 2 : 2 * ih0 - A.ph;
+        const int ows = MODE == 0 ? iw0 + A.pw - (R - 1) : MODE == 1 ? iw0 / 2 : 2 * iw0 - A.pw;
 
         __syncthreads();
         // dy[n, kt*64 .. +63, halo] as [pixel][64 k]; x[n, cg*64 .. +63, tile] as [pixel][64 c];
@@ -129,19 +162,24 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
         __syncthreads();
         if (!wave_active) continue;
 
-        for (int g0 = 0; g0 < TP; g0 += GP) {                // groups of GP pixels along a row
-            const int a = g0 / TW, b0 = g0 % TW;
+        for (int rp = 0; rp < TH / Cfg::RU; ++rp)
+        static_for<0, Cfg::RU>([&](auto PAR) __attribute__((always_inline)) {
+        constexpr int par = decltype(PAR)::value;            // row parity (MODE 1), else 0
+        const int a = rp * Cfg::RU + par;
+        for (int b0 = 0; b0 < TW; b0 += GP) {                // groups of GP pixels along the row
+            const int g0 = a * TW + b0;
             // non-zero mask of the group: bit 16*j + c for pixel j, channel c of the block
             const float mval = xT[(g0 + mpix) * 64 + cbl * 16 + mch];
             const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
             const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
             if ((mlo | mhi) == 0u) continue;                 // nothing to do for these 4 pixels x 16 channels
-            // dy window: rows a .. a+S-1, columns b0 .. b0+WC-1 of the halo, this lane's channel
-            float dyw[S][WC];
+            // window of the other operand's halo, this lane's channel
+            float dyw[WR][WC];
+            const int w0 = Cfg::wrow0(a) * HW + Cfg::wcol0(b0);
 #pragma unroll
-            for (int r = 0; r < S; ++r)
+            for (int r = 0; r < WR; ++r)
 #pragma unroll
-                for (int cc = 0; cc < WC; ++cc) dyw[r][cc] = dyT[((a + r) * HW + b0 + cc) * 64 + lane];
+                for (int cc = 0; cc < WC; ++cc) dyw[r][cc] = dyT[(w0 + r * HW + cc) * 64 + lane];
             // x of pixel 0 of the group: 8 channels, same address in all lanes
             const float4 *xq = reinterpret_cast<const float4 *>(xT + g0 * 64 + cbl * 16 + h * CH);
             float4 xlo = xq[0], xhi = xq[1];
@@ -165,8 +203,9 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
                             for (int v = 0; v < S; ++v)
 #pragma unroll
                                 for (int u = 0; u < R; ++u)
-                                    acc[ci][v * R + u] =
-                                        fmaf(xs[ci], dyw[S - 1 - v][j + R - 1 - u], acc[ci][v * R + u]);
+                                    if (Cfg::valid(par, j, v, u))
+                                        acc[ci][Cfg::slot(v, u)] = fmaf(xs[ci], dyw[Cfg::wr(par, v)][Cfg::wc(j, u)],
+                                                                        acc[ci][Cfg::slot(v, u)]);
                         }
                     });
                 }
@@ -175,6 +214,7 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
                 xhi = nhi;
             });
         }
+        });
     }
 
     if (wave_active && k < A.K) {
@@ -193,12 +233,12 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
 // v_mfma_f32_32x32x2_f32 with rows = 32 input channels, columns = 32 output channels, reduction
 // = 2 pixels per instruction; one accumulator block per filter tap.
 // ------------------------------------------------------------------------------------------
-template <int R, int S, int TH, int TW>
+template <int R, int S, int TH, int TW, int PSTEP = 1>
 __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *__restrict__ x,
                                                         const float *__restrict__ dy,
                                                         float *__restrict__ part)
 {
-    using Cfg = BwwCfg<R, S, TH, TW>;
+    using Cfg = BwwCfg<R, S, TH, TW, PSTEP>;
     constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
     static_assert(TW % 2 == 0, "pixel pairs must not straddle rows");
     __shared__ __attribute__((aligned(16))) float dyT[TP * 64];
@@ -226,7 +266,7 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
         const int th = t % A.tiles_h;
         const int n = t / A.tiles_h;
         const int oh0 = th * TH, ow0 = tw * TW;
-        const int ih0 = oh0 - A.ph, iw0 = ow0 - A.pw;
+        const int ih0 = oh0 * PSTEP - A.ph, iw0 = ow0 * PSTEP - A.pw;
 
         __syncthreads();
         for (int idx = threadIdx.x; idx < TP * 16; idx += 256) {
@@ -257,7 +297,7 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
             for (int v = 0; v < S; ++v)
 #pragma unroll
                 for (int u = 0; u < R; ++u) {
-                    const float av = xT[((a + v) * HW + (b + u)) * 64 + ch * 32 + l32];   // A[i = c][kk]
+                    const float av = xT[((a * PSTEP + v) * HW + (b * PSTEP + u)) * 64 + ch * 32 + l32];   // A[i = c][kk]
                     acc[v * R + u] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[v * R + u], 0, 0, 0);
                 }
         }
@@ -319,13 +359,15 @@ __global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__
 
 constexpr int kSparseTH = 8, kSparseTW = 8;
 constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
+// stride-2 layers: 4x8 tiles keep the strided halo of the other operand (9x17 pixels x 64 channels) in LDS
+constexpr int kS2TH = 4, kS2TW = 8;
 
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 {
     BwwArgs A;
     A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W;
-    A.OH = d.H + 2 * d.pad_h - d.S + 1;
-    A.OW = d.W + 2 * d.pad_w - d.R + 1;
+    A.OH = (d.H + 2 * d.pad_h - d.S) / d.stride_h + 1;
+    A.OW = (d.W + 2 * d.pad_w - d.R) / d.stride_w + 1;
     A.pw = d.pad_w; A.ph = d.pad_h;
     const int eh = tiles_over_input ? d.H : A.OH, ew = tiles_over_input ? d.W : A.OW;
     A.tiles_h = ceil_div(eh, TH);
@@ -361,8 +403,30 @@ hipError_t reduce(const st_conv_desc &d, const BwwArgs &A, const float *part, fl
 
 }  // namespace
 
+namespace {
+bool bww_s2(const st_conv_desc &d)
+{
+    return d.stride_w == 2 && d.stride_h == 2 && d.R == 3 && d.S == 3 && d.pad_w == 1 && d.pad_h == 1;
+}
+
+// stride 2, dy tested: the tested tile runs over dy (OH x OW, K channels), the halo over x
+BwwArgs make_args_s2_dy(const st_conv_desc &d)
+{
+    st_conv_desc e = d;
+    e.C = d.K; e.K = d.C;
+    e.H = (d.H + 2 * d.pad_h - d.S) / 2 + 1;
+    e.W = (d.W + 2 * d.pad_w - d.R) / 2 + 1;
+    e.stride_w = e.stride_h = 1;
+    BwwArgs A = make_args(e, kS2TH, kS2TW, true);
+    A.OH = d.H; A.OW = d.W;                         // size of the halo operand (x)
+    A.pw = d.pad_w; A.ph = d.pad_h;
+    return A;
+}
+}  // namespace
+
 bool bww_fast_supported(const st_conv_desc &d)
 {
+    if (bww_s2(d)) return (long long)d.N * ceil_div(d.H, 4) * ceil_div(d.W, 8) <= 0x7fffffffLL;
     if (d.stride_w != 1 || d.stride_h != 1) return false;
     const long long units = (long long)d.N * ceil_div(d.H + 2 * d.pad_h, 8) * ceil_div(d.W + 2 * d.pad_w, 16);
     if (units > 0x7fffffffLL) return false;
@@ -373,11 +437,12 @@ bool bww_fast_supported(const st_conv_desc &d)
 
 size_t bww_sparse_workspace(const st_conv_desc &d)
 {
-    return partial_bytes(d, make_args(d, kSparseTH, kSparseTW, true));
+    return partial_bytes(d, make_args(d, kSparseTH, kSparseTW, true));       // same tiles for both strides
 }
 
 size_t bww_dense_workspace(const st_conv_desc &d)
 {
+    if (bww_s2(d)) return partial_bytes(d, make_args(d, kS2TH, kS2TW, false));
     return partial_bytes(d, make_args(d, kDenseTH, kDenseTW, false));
 }
 
@@ -387,6 +452,11 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
     const BwwArgs A = make_args(d, kSparseTH, kSparseTW, true);
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
+    if (bww_s2(d)) {
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 1>), grid, dim3(512), 0, s, A, x, dy, part);
+        hipError_t err = hipGetLastError();
+        return err != hipSuccess ? err : reduce(d, A, ws, dw, s);
+    }
     if (d.R == 3)
         hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
     else
@@ -415,11 +485,13 @@ st_conv_desc swapped_desc(const st_conv_desc &d)
 
 bool bww_dy_fast_supported(const st_conv_desc &d)
 {
+    if (bww_s2(d)) return bww_fast_supported(d);
     return bww_fast_supported(d) && d.pad_h <= d.S - 1 && d.pad_w <= d.R - 1 && bww_fast_supported(swapped_desc(d));
 }
 
 size_t bww_sparse_dy_workspace(const st_conv_desc &d)
 {
+    if (bww_s2(d)) return (size_t)make_args_s2_dy(d).splits * d.K * d.C * d.S * d.R * sizeof(float);
     const st_conv_desc e = swapped_desc(d);
     const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
     return (size_t)A.splits * d.K * d.C * d.S * d.R * sizeof(float);        // always staged, even for one split
@@ -428,6 +500,17 @@ size_t bww_sparse_dy_workspace(const st_conv_desc &d)
 hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                                 float *ws, hipStream_t s)
 {
+    if (bww_s2(d)) {
+        const BwwArgs A = make_args_s2_dy(d);
+        dim3 grid(A.splits, ceil_div(A.K, 64) * A.cgroups);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, ws);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        const size_t total = (size_t)d.K * d.C * d.S * d.R;
+        hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ws, dw,
+                           d.K, d.C, d.S, d.R, A.splits);
+        return hipGetLastError();
+    }
     const st_conv_desc e = swapped_desc(d);
     const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
     dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
@@ -446,6 +529,14 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                             float *ws, hipStream_t s)
 {
+    if (bww_s2(d)) {
+        const BwwArgs A2 = make_args(d, kS2TH, kS2TW, false);
+        dim3 grid2(A2.splits, ceil_div(d.K, 64) * A2.cgroups);
+        hipLaunchKernelGGL((bww_dense_kernel<3, 3, kS2TH, kS2TW, 2>), grid2, dim3(256), 0, s, A2, x, dy,
+                           A2.splits == 1 ? dw : ws);
+        hipError_t err = hipGetLastError();
+        return err != hipSuccess ? err : reduce(d, A2, ws, dw, s);
+    }
     const BwwArgs A = make_args(d, kDenseTH, kDenseTW, false);
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);

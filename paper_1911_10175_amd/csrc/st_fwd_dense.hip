@@ -31,24 +31,43 @@ __device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, i
 
 // TWD = tile width: 8 (8 rows), 14 (4 rows) or 28 (2 rows); a tile holds at most 64 pixels, i.e.
 // two 32-row MFMA blocks; with 14 or 28 columns the last 8 rows of the second block are padding.
-template <int R, int S, int TWD>
+//
+// MODE selects how tile pixels, taps and input samples relate:
+//   0  unit stride: tile pixel (ty,tx), tap (v,u) reads halo pixel (ty+v, tx+u).
+//   1  stride 2 (FWD of the stride-2 3x3 layers): halo pixel (2*ty+v, 2*tx+u).
+//   2  BWI of a stride-2 3x3 layer with padding 1, one launch per parity class (PI,PJ) of the dx
+//      positions: the tile is an 8x8 (or 4x14, 2x28) block of the positions (2*i+PI, 2*j+PJ); only
+//      the taps whose grid position holds a dy sample contribute (SparseTrain Sec. 3.3): for PI = 0
+//      the middle tap reading dy row i, for PI = 1 the outer taps reading dy rows i and i+1; the
+//      same along the width.  1, 2, 2 and 4 taps for the four classes instead of 9.
+template <int R, int S, int TWD, int MODE = 0, int PI = 0, int PJ = 0>
 struct FwdDenseCfg {
     static constexpr int TW = TWD, TH = 64 / TWD, NPIX = TH * TW;
-    static constexpr int HH = TH + S - 1, HW = TW + R - 1, HP = HH * HW;
+    static constexpr int PSTEP = MODE == 1 ? 2 : 1;                 // halo pixels between neighbouring tile pixels
+    static constexpr int NV = MODE == 2 ? (PI ? 2 : 1) : S, NU = MODE == 2 ? (PJ ? 2 : 1) : R, NT = NV * NU;
+    static constexpr int HH = MODE == 2 ? TH + PI : (TH - 1) * PSTEP + S;
+    static constexpr int HW = MODE == 2 ? TW + PJ : (TW - 1) * PSTEP + R;
+    static constexpr int HP = HH * HW;
+    // tap t = (kv, ku): halo offset (dv, du) and index of the filter tap in the reformatted copy
+    static constexpr int dv(int t) { return t / NU; }
+    static constexpr int du(int t) { return t % NU; }
+    static constexpr int fv(int t) { return MODE == 2 ? (PI ? 2 * (t / NU) : 1) : t / NU; }
+    static constexpr int fu(int t) { return MODE == 2 ? (PJ ? 2 * (t % NU) : 1) : t % NU; }
+    static constexpr int ftap(int t) { return fv(t) * R + fu(t); }
     static constexpr int XST = 20;                  // floats per staged pixel (16 channels + 4 pad)
     static constexpr int BUF = ((HP * XST + 63) / 64) * 64;   // floats per halo buffer
 };
 
 // KQ = column blocks (of 32 output channels) per workgroup: 1, 2 or 4; TQ = 4/KQ pixel tiles.
-template <int R, int S, int KQ, int TWD>
+template <int R, int S, int KQ, int TWD, int MODE = 0, int PI = 0, int PJ = 0>
 __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *__restrict__ in,
                                                            const float *__restrict__ wd,
                                                            float *__restrict__ out, int tiles_w,
                                                            int tiles_h, int kgroups, int total_tiles)
 {
-    using Cfg = FwdDenseCfg<R, S, TWD>;
+    using Cfg = FwdDenseCfg<R, S, TWD, MODE, PI, PJ>;
     constexpr int TH = Cfg::TH, TW = Cfg::TW, HW = Cfg::HW, HP = Cfg::HP, XST = Cfg::XST, BUF = Cfg::BUF;
-    constexpr int TAPS = S * R, TQ = 4 / KQ, NPIX = Cfg::NPIX;
+    constexpr int TAPS = S * R, TQ = 4 / KQ, NPIX = Cfg::NPIX, NT = Cfg::NT, PSTEP = Cfg::PSTEP;
     constexpr int NLD = (HP * 4 + KQ * 64 - 1) / (KQ * 64);      // float4 loads per lane and block
     __shared__ __attribute__((aligned(16))) float lds_all[2][TQ][BUF];
 
@@ -61,8 +80,8 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
     const int tw = t % tiles_w; t /= tiles_w;
     const int th = t % tiles_h;
     const int n = t / tiles_h;
-    const int oh0 = th * TH, ow0 = tw * TW;
-    const int ih0 = oh0 - g.ph, iw0 = ow0 - g.pw;
+    const int oh0 = th * TH, ow0 = tw * TW;         // MODE 2: in units of the parity class's own grid
+    const int ih0 = MODE == 2 ? oh0 : oh0 * PSTEP - g.ph, iw0 = MODE == 2 ? ow0 : ow0 * PSTEP - g.pw;
     const int CiB = g.Ci / kBlk, KoB = g.Ko / kBlk;
     const int kb32 = kg * KQ + kqi;                 // this wavefront's column block
     const bool k_ok = kb32 * 32 < g.Ko;
@@ -90,7 +109,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
 #pragma unroll
     for (int pb = 0; pb < 2; ++pb) {
         const int p = min(pb * 32 + l32, NPIX - 1);        // padding rows read a valid pixel; never stored
-        apix[pb] = (p / TW) * HW + (p % TW);
+        apix[pb] = (p / TW) * PSTEP * HW + (p % TW) * PSTEP;
     }
 
     // halo staging: the KQ wavefronts of a tile split its HP*4 float4 among their KQ*64 lanes
@@ -117,22 +136,23 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
     };
 
     constexpr int kWaitOlder = 2 | (0x7 << 4) | (0xF << 8);       // vmcnt(2): all but the 2 newest loads
-    const int nsteps = CiB * TAPS;
     float bcur[8], bnxt[8];
     float4 hreg[NLD];
     load_halo(0, hreg);
     store_halo(lds_all[0][tqi], hreg);
-    load_b(0, bcur);
+    load_b(Cfg::ftap(0), bcur);
     __syncthreads();
 
     for (int cb = 0; cb < CiB; ++cb) {
         const float *lds = lds_all[cb & 1][tqi];
 #pragma unroll
-        for (int v = 0; v < S; ++v)
-#pragma unroll
-            for (int u = 0; u < R; ++u) {
-                const int step = cb * TAPS + v * R + u;
-                load_b(min(step + 1, nsteps - 1), bnxt);        // next step's filters fly during this step's MFMAs
+        for (int tp = 0; tp < NT; ++tp) {
+            {
+                const int v = Cfg::dv(tp), u = Cfg::du(tp);
+                // next step's filters fly during this step's MFMAs (the last step re-reads its own)
+                const int nstep = tp + 1 < NT ? cb * TAPS + Cfg::ftap(tp + 1 < NT ? tp + 1 : 0)
+                                              : min(cb + 1, CiB - 1) * TAPS + Cfg::ftap(0);
+                load_b(nstep, bnxt);
                 __builtin_amdgcn_sched_barrier(0);              // keep these loads ahead of the MFMAs below
                 float a[2][8];
 #pragma unroll
@@ -147,7 +167,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
                 __builtin_amdgcn_sched_barrier(0);
                 // The next block's halo is requested here, after the wait, so that the first wait
                 // that covers these loads is the one of the next tap: they land during the MFMAs.
-                if (v == 0 && u == 0 && cb + 1 < CiB) {
+                if (tp == 0 && cb + 1 < CiB) {
                     load_halo(cb + 1, hreg);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -161,6 +181,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
 #pragma unroll
                 for (int j = 0; j < 8; ++j) bcur[j] = bnxt[j];
             }
+        }
         if (cb + 1 < CiB) store_halo(lds_all[(cb + 1) & 1][tqi], hreg);
         __syncthreads();
     }
@@ -174,7 +195,8 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int p = pb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                const int oh = oh0 + p / TW, ow = ow0 + p % TW;
+                const int oh = MODE == 2 ? 2 * (oh0 + p / TW) + PI : oh0 + p / TW;
+                const int ow = MODE == 2 ? 2 * (ow0 + p % TW) + PJ : ow0 + p % TW;
                 if (p < NPIX && oh < g.Ho && ow < g.Wo)
                     out[act_off(n, kb, oh, ow, KoB, g.Ho, g.Wo) + ki] = acc[pb][r];
             }
@@ -216,27 +238,61 @@ __global__ __launch_bounds__(256) void reformat_filters_kernel(int Ko, int Ci, i
     wd[i] = val;
 }
 
-template <int R, int S, int KQ, int TWD>
+template <int R, int S, int KQ, int TWD, int MODE = 0, int PI = 0, int PJ = 0>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
-    using Cfg = FwdDenseCfg<R, S, TWD>;
+    using Cfg = FwdDenseCfg<R, S, TWD, MODE, PI, PJ>;
     constexpr int TQ = 4 / KQ;
-    const int tiles_w = ceil_div(g.Wo, Cfg::TW), tiles_h = ceil_div(g.Ho, Cfg::TH);
+    // MODE 2 tiles the positions of one parity class: (Ho - PI + 1) / 2 rows, (Wo - PJ + 1) / 2 columns
+    const int rows = MODE == 2 ? (g.Ho - PI + 1) / 2 : g.Ho, cols = MODE == 2 ? (g.Wo - PJ + 1) / 2 : g.Wo;
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const int tiles_w = ceil_div(cols, Cfg::TW), tiles_h = ceil_div(rows, Cfg::TH);
     const long long total_tiles = (long long)tiles_w * tiles_h * g.N;
     const int kgroups = ceil_div(g.Ko, 32 * KQ);
     const long long blocks = (total_tiles + TQ - 1) / TQ * kgroups;
     if (total_tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ, TWD>), dim3((unsigned)blocks), dim3(256), 0, s, g, in, wd, out,
+    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ, TWD, MODE, PI, PJ>), dim3((unsigned)blocks), dim3(256), 0, s, g, in, wd, out,
                        tiles_w, tiles_h, kgroups, (int)total_tiles);
     return hipGetLastError();
 }
 
-template <int R, int S, int TWD>
+template <int R, int S, int TWD, int MODE = 0, int PI = 0, int PJ = 0>
 hipError_t launch_kq(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
-    if (g.Ko > 64) return launch_cfg<R, S, 4, TWD>(g, in, wd, out, s);
-    if (g.Ko > 32) return launch_cfg<R, S, 2, TWD>(g, in, wd, out, s);
-    return launch_cfg<R, S, 1, TWD>(g, in, wd, out, s);
+    // the stride-2 halo is four times larger: one pixel tile per workgroup is all that fits in LDS
+    // (with at most 64 output channels some of its four wavefronts then only help staging)
+    if constexpr (MODE == 1) {
+        return launch_cfg<R, S, 4, TWD, MODE, PI, PJ>(g, in, wd, out, s);
+    } else {
+        if (g.Ko > 64) return launch_cfg<R, S, 4, TWD, MODE, PI, PJ>(g, in, wd, out, s);
+        if (g.Ko > 32) return launch_cfg<R, S, 2, TWD, MODE, PI, PJ>(g, in, wd, out, s);
+        return launch_cfg<R, S, 1, TWD, MODE, PI, PJ>(g, in, wd, out, s);
+    }
+}
+
+// stride-2 FWD: 8x8 output tiles (17x17 input halo), 4x14 tiles (9x29) for 14-wide outputs
+hipError_t launch_s2_fwd(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
+{
+    if (g.Wo % 8 != 0 && g.Wo % 14 == 0 && g.Ho % 4 <= g.Ho % 8) return launch_kq<3, 3, 14, 1>(g, in, wd, out, s);
+    return launch_kq<3, 3, 8, 1>(g, in, wd, out, s);
+}
+
+// BWI of a stride-2 layer: the four parity classes of the dx positions, one launch each
+template <int TWD>
+hipError_t launch_s2_bwi_tw(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
+{
+    hipError_t e = launch_kq<3, 3, TWD, 2, 1, 1>(g, in, wd, out, s);        // 4 taps: the longest first
+    if (e == hipSuccess) e = launch_kq<3, 3, TWD, 2, 1, 0>(g, in, wd, out, s);
+    if (e == hipSuccess) e = launch_kq<3, 3, TWD, 2, 0, 1>(g, in, wd, out, s);
+    if (e == hipSuccess) e = launch_kq<3, 3, TWD, 2, 0, 0>(g, in, wd, out, s);
+    return e;
+}
+
+hipError_t launch_s2_bwi(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
+{
+    const int cols = g.Wo / 2;                      // columns of a parity class (up to one more for PJ = 0)
+    if (cols % 8 != 0 && cols % 14 == 0) return launch_s2_bwi_tw<14>(g, in, wd, out, s);
+    return launch_s2_bwi_tw<8>(g, in, wd, out, s);
 }
 
 template <int R, int S>
@@ -252,7 +308,10 @@ hipError_t launch_rs(const Geom &g, const float *in, const float *wd, float *out
 
 bool fwd_dense_supported(const Geom &g)
 {
-    if (g.sw != 1 || g.sh != 1 || g.uw != 1 || g.uh != 1) return false;
+    if (g.sw != g.sh || g.uw != g.uh) return false;
+    if (g.sw == 2 && g.uw == 1) return g.R == 3 && g.S == 3 && g.pw <= 2 && g.ph <= 2;
+    if (g.sw == 1 && g.uw == 2) return g.R == 3 && g.S == 3 && g.pw == 1 && g.ph == 1;
+    if (g.sw != 1 || g.uw != 1) return false;
     if (g.R == 3 && g.S == 3) return g.pw <= 2 && g.ph <= 2;
     if (g.R == 1 && g.S == 1) return g.pw == 0 && g.ph == 0;
     return false;
@@ -274,6 +333,8 @@ hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w
 
 hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
+    if (g.sw == 2) return launch_s2_fwd(g, in, wd, out, s);
+    if (g.uw == 2) return launch_s2_bwi(g, in, wd, out, s);
     if (g.R == 3 && g.S == 3) return launch_rs<3, 3>(g, in, wd, out, s);
     if (g.R == 1 && g.S == 1) {
         // minibatch-wide pixel numbering of the pointwise kernel is kept in int

@@ -81,7 +81,7 @@ def test_workspace_query_and_rejection():
         assert st.st_conv_bww_dy(dd, 256, 256, 256, ws=None, check=False) == 4
         assert st.st_conv_bww_dy(dd, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
     # shapes served by the generic kernel need none
-    assert st.st_conv_workspace_bytes(st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 2, 2, 1, 1), st.ST_PASS_BWW_DY) == 0
+    assert st.st_conv_workspace_bytes(st.ConvDesc(1, 16, 16, 8, 8, 5, 5, 1, 1, 2, 2), st.ST_PASS_BWW_DY) == 0
     assert st.st_conv_workspace_bytes(d, 7) == 0
 
 

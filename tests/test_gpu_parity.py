@@ -63,8 +63,8 @@ SMALL = [
     # 1x1
     ("1x1_k128", Geom(2, 64, 128, 12, 12, 1, 1), 0.4, 0.5),
     ("1x1_k64", Geom(2, 256, 64, 9, 11, 1, 1), 0.55, 0.5),
-    # shapes only the generic kernels cover
     ("3x3_stride2", Geom(2, 32, 32, 14, 14, 3, 3, 2, 2, 1, 1), 0.5, 0.5),
+    # shapes only the generic kernels cover
     ("5x5_pad2", Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2), 0.5, 0.5),
     ("r3_s1_stride_1x2", Geom(1, 32, 16, 8, 11, 3, 1, 2, 1, 1, 0), 0.5, 0.5),
     ("1x1_stride2", Geom(1, 32, 32, 9, 9, 1, 1, 2, 2, 0, 0), 0.5, 0.5),
