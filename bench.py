@@ -28,7 +28,7 @@ PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
 # HBM traffic per launch of the dominant kernel (fwd_sparse_kernel on this workload) from two
 # rocprofv3 --pmc runs, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 (factors from a 256 MiB copy of known
 # size): 75231.9 KiB * 2 + 78398.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = int((75231.9 * 2.0 + 78398.0) * 1024)
+MEASURED_TRAFFIC_BYTES = int((75590.2 * 2.0 + 84656.9) * 1024)
 
 
 def write_config_table(path, st, stgen, torch, dev, stream):
@@ -64,7 +64,7 @@ def write_config_table(path, st, stgen, torch, dev, stream):
     rows = []
 
     def run(cfg, L, px, pdy):
-        d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
+        d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, L.stride, L.stride, L.pad, L.pad)
         x = relu_sparse((L.N, L.C // 16, L.H, L.W, 16), px)
         dy = masked((L.N, L.K // 16, L.OH, L.OW, 16), pdy)
         w = torch.randn((L.K // 16, L.C // 16, L.S, L.R, 16, 16), device=dev) * math.sqrt(2.0 / (L.C * L.R * L.S))
@@ -83,9 +83,17 @@ def write_config_table(path, st, stgen, torch, dev, stream):
             ts = timeit(lambda: fs(d, a, b, o, wss, stream))
             td = timeit(lambda: fd(d, a, b, o, wsd, stream))
             eff = d.flops / ts / 1e9
-            rows.append(f"| {cfg} | {L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S} N={L.N} | {name} | {z:.2f} | {ts * 1e3:.0f} | "
+            label = f"{L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S}" + (f"/{L.stride}" if L.stride != 1 else "") + f" N={L.N}"
+            rows.append(f"| {cfg} | {label} | {name} | {z:.2f} | {ts * 1e3:.0f} | "
                         f"{td * 1e3:.0f} | {eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | "
                         f"{d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} |")
+            if name == "BWW":       # the same tensor with the zero test on dy (st_conv_bww_dy); same dense control
+                wsy = ws(st.ST_PASS_BWW_DY, False)
+                ty = timeit(lambda: st.st_conv_bww_dy(d, a, b, o, wsy, stream))
+                effy = d.flops / ty / 1e9
+                rows.append(f"| {cfg} | {label} | BWW(dy) | {zdy:.2f} | {ty * 1e3:.0f} | {td * 1e3:.0f} | {effy:.1f} | "
+                            f"{effy * (1 - zdy) / PEAK_FP32_VECTOR:.3f} | {d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | "
+                            f"{td / ty:.2f} |")
         del x, dy, w, y, dx, dw
 
     run(3, stgen.RESNET3_2, stgen.RESNET3_2.p_x, stgen.RESNET3_2.p_dy)
@@ -96,7 +104,16 @@ def write_config_table(path, st, stgen, torch, dev, stream):
             if L.name in ("vgg3_3", "vgg4_3", "vgg5_2", "vgg5_3"):      # same shapes as 3_2, 4_2, 5_1
                 continue
             run(5, L, p, p)
+    # every row of the paper's Table 1 (stride-2 and the late 1x1 layers included) at 50 % zeros
+    for L in stgen.table1_layers(32, 0.5, 0.5):
+        if L.name == "vgg1_2":
+            L = stgen.Layer(L.name, 16, L.C, L.K, L.H, L.W, L.R, L.S, L.pad, 0.5, 0.5, L.stride)
+        run("T1", L, 0.5, 0.5)
     with open(path, "w") as f:
+        f.write("# Per-workload timings: `python bench.py --no-cpu --no-sweep --table <this file>` on one MI355X\n\n"
+                "Median of 7 launches (HIP events) per entry point; inputs drawn on the device with the benchmark's\n"
+                "distributions. config 3 = ResNet-34 block, 4 = ResNet-50 bottleneck, 5 = VGG16 stack at 0-90 % zeros,\n"
+                "T1 = every layer of the paper's Table 1 at 50 % zeros. BWW tests x, BWW(dy) tests dy.\n\n")
         f.write("| config | layer | pass | zeros of tested operand | sparse us | dense us | effective TFLOP/s | "
                 "executed / 157.3 (fp32 vector peak) | dense / 157.3 (MFMA peak) | speed-up |\n")
         f.write("|---|---|---|---|---|---|---|---|---|---|\n")

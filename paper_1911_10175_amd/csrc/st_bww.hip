@@ -340,21 +340,23 @@ __global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__
                                                                  float *__restrict__ dw, int K, int C, int S,
                                                                  int R, int splits)
 {
+    // one workgroup per 16x16 block (k block, c block, tap) of dw: the source block [ki][ci] is read
+    // row by row (coalesced) and summed over the splits, then written transposed through LDS
+    __shared__ float tile[kBlk][kBlk + 1];
     const size_t total = (size_t)K * C * S * R;
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    size_t t = i;
-    const int ki = t % kBlk; t /= kBlk;
-    const int ci = t % kBlk; t /= kBlk;
+    int t = blockIdx.x;
     const int u = t % R; t /= R;
     const int v = t % S; t /= S;
     const int cb = t % (C / kBlk);
-    const int kb = (int)(t / (C / kBlk));
+    const int kb = t / (C / kBlk);
+    const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
     const size_t src = ((((size_t)cb * (K / kBlk) + kb) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) +
-                       ki * kBlk + ci;
+                       a * kBlk + b;                                       // element [ki = a][ci = b]
     float sum = part[src];
     for (int p = 1; p < splits; ++p) sum += part[(size_t)p * total + src];
-    dw[i] = sum;
+    tile[a][b] = sum;
+    __syncthreads();
+    dw[((((size_t)kb * (C / kBlk) + cb) * S + v) * R + u) * (kBlk * kBlk) + a * kBlk + b] = tile[b][a];   // [ci = a][ki = b]
 }
 
 constexpr int kSparseTH = 8, kSparseTW = 8;
@@ -507,7 +509,7 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
         const size_t total = (size_t)d.K * d.C * d.S * d.R;
-        hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ws, dw,
+        hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, ws, dw,
                            d.K, d.C, d.S, d.R, A.splits);
         return hipGetLastError();
     }
@@ -521,7 +523,7 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     const size_t total = (size_t)d.K * d.C * d.S * d.R;
-    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, ws, dw,
+    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, ws, dw,
                        d.K, d.C, d.S, d.R, A.splits);
     return hipGetLastError();
 }

@@ -136,24 +136,27 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
         // the same in every lane (a broadcast): each lane then holds the four inputs in registers
         // and the multiply-adds need no cross-lane move.  The next group is in flight while the
         // current one is processed; LDS reads return in order, so lgkmcnt(1) means "all but the
-        // newest read have arrived".
+        // newest read have arrived".  (Staging the filters in LDS, shared by the four wavefronts of
+        // a workgroup, was measured and is slower at every sparsity: the barriers cost more than
+        // the L2 traffic they save.)
         const float4 *lds4 = reinterpret_cast<const float4 *>(lds + ci * PST);
         constexpr int NG = (HP + 3) / 4;
         float4 xq[2];                       // two groups of values alternate (no register copies)
         xq[0] = lds4[0];
         static_for<0, NG>([&](auto G) __attribute__((always_inline)) {
             constexpr int gidx = decltype(G)::value;
+            if constexpr (gidx + 1 < NG) xq[(gidx + 1) % 2] = lds4[gidx + 1];
+            // a group whose four pixels are all zero costs one test instead of four, and does not
+            // wait for its values either
+            constexpr unsigned gmask = 0xFu << ((gidx * 4) % 32);
+            if (__builtin_expect((m32[(gidx * 4) / 32] & gmask) != 0u, 1)) {
             if constexpr (gidx + 1 < NG) {
-                xq[(gidx + 1) % 2] = lds4[gidx + 1];
                 __builtin_amdgcn_s_waitcnt(0xC17F);      // lgkmcnt(1)
             } else {
                 __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
             }
             const float4 cur = xq[gidx % 2];
             const float xg[4] = {cur.x, cur.y, cur.z, cur.w};
-            // a group whose four pixels are all zero costs one test instead of four
-            constexpr unsigned gmask = 0xFu << ((gidx * 4) % 32);
-            if (__builtin_expect((m32[(gidx * 4) / 32] & gmask) != 0u, 1))
             // one branch per halo pixel; all register indices below are compile-time constants
             static_for<0, 4>([&](auto J) __attribute__((always_inline)) {
                 constexpr int i = gidx * 4 + decltype(J)::value;
@@ -177,6 +180,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
                     }
                 }
             });
+            }
         });
     };
 
