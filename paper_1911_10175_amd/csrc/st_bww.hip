@@ -319,31 +319,262 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
     }
 }
 
-// dw[i] = sum over splits of part[s][i], in split order
-__global__ __launch_bounds__(256) void bww_reduce_kernel(const float4 *__restrict__ part,
-                                                         float4 *__restrict__ dw, size_t n4, int splits)
+// ------------------------------------------------------------------------------------------
+// 1x1 layers (unit stride, no padding): dw[k][c] = sum over all N*H*W pixels of dy[p][k] * x[p][c],
+// a matrix product with the pixels as the reduction dimension (Sec. 5.2 of the paper).  Pixels are
+// numbered across the minibatch and cut into chunks of PWP; `units` counts chunks.
+// ------------------------------------------------------------------------------------------
+constexpr int kPwP = 32;            // pixels per staged chunk
+
+// Dense: workgroup = 128 input channels x 128 output channels, wavefront = 64 x 64 (four 32x32 MFMA
+// blocks), so that a staged pixel is used for four times as many MFMAs as in the tap-per-block
+// kernel above; the next chunk is fetched into registers while the current one is multiplied.
+__global__ __launch_bounds__(256) void pw_bww_dense_kernel(BwwArgs A, const float *__restrict__ x,
+                                                           const float *__restrict__ dy,
+                                                           float *__restrict__ part)
 {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n4) return;
-    float4 s = part[i];
-    for (int p = 1; p < splits; ++p) {
-        const float4 v = part[(size_t)p * n4 + i];
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    constexpr int P = kPwP, CW = 128;                   // channels of either operand per workgroup
+    __shared__ __attribute__((aligned(16))) float xs[P * CW];
+    __shared__ __attribute__((aligned(16))) float ds[P * CW];
+
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int l32 = lane % 32, half = lane / 32;
+    const int wk = wave % 2, wc = wave / 2;
+    const int split = blockIdx.x;
+    const int kt = blockIdx.y / A.cgroups, cg = blockIdx.y % A.cgroups;     // groups of 128 channels here
+    const int CB = A.C / kBlk, KB = A.K / kBlk;
+    const int HW = A.H * A.W;
+    const long long total_px = (long long)A.N * HW;
+
+    floatx16 acc[2][2];                                 // [c block of 32][k block of 32]
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int u0 = (int)((long long)A.units * split / A.splits);
+    const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
+
+    // staging slots of this thread: 4 float4 of x and 4 of dy per chunk; slot = (pixel, 4 channels)
+    float4 rx[4], rd[4];
+    auto fetch = [&](int unit) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int idx = jj * 256 + (int)threadIdx.x;
+            const int pix = idx >> 5, q = idx & 31;                 // 32 float4 = 128 channels per pixel
+            const long long gp = (long long)unit * P + pix;
+            rx[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+            rd[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gp < total_px) {
+                const int n = (int)(gp / HW), p = (int)(gp % HW);
+                const int cb = cg * 8 + (q >> 2), kb = kt * 8 + (q >> 2);
+                if (cb < CB) rx[jj] = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cb) * HW + p) * kBlk + (q & 3) * 4);
+                if (kb < KB) rd[jj] = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
+            }
+        }
+    };
+    auto stash = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int idx = jj * 256 + (int)threadIdx.x;
+            *reinterpret_cast<float4 *>(xs + idx * 4) = rx[jj];     // [pixel][128 c]
+            *reinterpret_cast<float4 *>(ds + idx * 4) = rd[jj];     // [pixel][128 k]
+        }
+    };
+
+    if (u0 < u1) fetch(u0);
+    for (int unit = u0; unit < u1; ++unit) {
+        __syncthreads();                                // the previous chunk is no longer read
+        stash();
+        __syncthreads();
+        if (unit + 1 < u1) fetch(unit + 1);             // in flight during the MFMAs below
+#pragma unroll 4
+        for (int pp = 0; pp < P / 2; ++pp) {
+            const int p = 2 * pp + half;                // A[i = c][kk = half], B[kk = half][j = k]
+            float av[2], bv[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) av[i] = xs[p * CW + wc * 64 + i * 32 + l32];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) bv[j] = ds[p * CW + wk * 64 + j * 32 + l32];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
     }
-    dw[i] = s;
+
+    // D[i = c][j = k]: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
+    float *pbase = part + (size_t)split * A.K * A.C;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int k = kt * CW + wk * 64 + j * 32 + l32;
+        if (k >= A.K) continue;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int c = cg * CW + wc * 64 + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                if (c < A.C)
+                    pbase[((size_t)(k / kBlk) * CB + c / kBlk) * (kBlk * kBlk) + (c % kBlk) * kBlk + k % kBlk] = acc[i][j][r];
+            }
+    }
 }
 
-// The same sum for the run with the operand roles swapped (BWW that tests dy): the partials hold
-// dw'[c][k][S-1-v][R-1-u] in the filter layout of a layer with C and K exchanged; this kernel adds
-// them and writes dw[k][c][v][u] in the library layout.
+// Zero-skipping: lane = KPL output channels (k, k+64, ...), wavefront = 8 input channels, workgroup =
+// 8 wavefronts = 64 input channels, as in bww_sparse_kernel but with KPL accumulators per tested
+// element instead of R*S: without taps, the number of multiply-adds a zero saves is the number of
+// output channels a lane owns (T = K/64 up to 4), the 1x1 analogue of T = Q/V in Sec. 5.2.
+template <int KPL>
+__global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
+                                                               const float *__restrict__ dy,
+                                                               float *__restrict__ part)
+{
+    constexpr int P = kPwP, CH = 8, GP = 4, KW = 64 * KPL;
+    __shared__ __attribute__((aligned(16))) float dyT[P * KW];
+    __shared__ __attribute__((aligned(16))) float xT[P * 64];
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int lane = threadIdx.x % kWave;
+    const int split = blockIdx.x;
+    const int kt = blockIdx.y / A.cgroups, cg = blockIdx.y % A.cgroups;     // kt: groups of KW, cg: of 64
+    const int CB = A.C / kBlk, KB = A.K / kBlk;
+    const int cbl = wave >> 1, h = wave & 1;
+    const int cb = cg * 4 + cbl;
+    const bool wave_active = cb < CB;
+    const int HW = A.H * A.W;
+    const long long total_px = (long long)A.N * HW;
+
+    float acc[CH][KPL];
+#pragma unroll
+    for (int ci = 0; ci < CH; ++ci)
+#pragma unroll
+        for (int j = 0; j < KPL; ++j) acc[ci][j] = 0.f;
+
+    const int u0 = (int)((long long)A.units * split / A.splits);
+    const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
+    const int mpix = lane >> 4, mch = lane & 15;
+
+    for (int unit = u0; unit < u1; ++unit) {
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < P * (KW / 4); idx += 512) {
+            const int pix = idx / (KW / 4), q = idx % (KW / 4);
+            const long long gp = (long long)unit * P + pix;
+            const int kb = kt * (KW / kBlk) + (q >> 2);
+            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gp < total_px && kb < KB) {
+                const int n = (int)(gp / HW), p = (int)(gp % HW);
+                val = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
+            }
+            *reinterpret_cast<float4 *>(dyT + pix * KW + q * 4) = val;
+        }
+        for (int idx = threadIdx.x; idx < P * 16; idx += 512) {
+            const int pix = idx >> 4, q = idx & 15;
+            const long long gp = (long long)unit * P + pix;
+            const int cbq = cg * 4 + (q >> 2);
+            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gp < total_px && cbq < CB) {
+                const int n = (int)(gp / HW), p = (int)(gp % HW);
+                val = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cbq) * HW + p) * kBlk + (q & 3) * 4);
+            }
+            *reinterpret_cast<float4 *>(xT + pix * 64 + q * 4) = val;
+        }
+        __syncthreads();
+        if (!wave_active) continue;
+
+        for (int g0 = 0; g0 < P; g0 += GP) {
+            const float mval = xT[(g0 + mpix) * 64 + cbl * 16 + mch];
+            const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
+            const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
+            if ((mlo | mhi) == 0u) continue;
+            float dyw[GP][KPL];
+#pragma unroll
+            for (int j = 0; j < GP; ++j)
+#pragma unroll
+                for (int q = 0; q < KPL; ++q) dyw[j][q] = dyT[(g0 + j) * KW + q * 64 + lane];
+            const float4 *xq = reinterpret_cast<const float4 *>(xT + g0 * 64 + cbl * 16 + h * CH);
+            float4 xlo = xq[0], xhi = xq[1];
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            static_for<0, GP>([&](auto J) __attribute__((always_inline)) {
+                constexpr int j = decltype(J)::value;
+                float4 nlo = xlo, nhi = xhi;
+                if constexpr (j + 1 < GP) {
+                    nlo = xq[(j + 1) * 16];
+                    nhi = xq[(j + 1) * 16 + 1];
+                }
+                const float xv[CH] = {xlo.x, xlo.y, xlo.z, xlo.w, xhi.x, xhi.y, xhi.z, xhi.w};
+                const unsigned mw = (j < 2) ? mlo : mhi;
+                constexpr int sh = (j % 2) * 16;
+                const unsigned bits = (mw >> sh) >> (h * CH) & 0xFFu;
+                if (__builtin_expect(bits != 0u, 1)) {
+                    static_for<0, CH>([&](auto CI) __attribute__((always_inline)) {
+                        constexpr int ci = decltype(CI)::value;
+                        if (__builtin_expect((bits & (1u << ci)) != 0u, 1)) {
+#pragma unroll
+                            for (int q = 0; q < KPL; ++q) acc[ci][q] = fmaf(xv[ci], dyw[j][q], acc[ci][q]);
+                        }
+                    });
+                }
+                if constexpr (j + 1 < GP) __builtin_amdgcn_s_waitcnt(0xC07F);
+                xlo = nlo;
+                xhi = nhi;
+            });
+        }
+    }
+
+    if (wave_active) {
+        float *pbase = part + (size_t)split * A.K * A.C;
+#pragma unroll
+        for (int q = 0; q < KPL; ++q) {
+            const int k = kt * KW + q * 64 + lane;
+            if (k >= A.K) continue;
+            float *p = pbase + ((size_t)(k / kBlk) * CB + cb) * (kBlk * kBlk) + (h * CH) * kBlk + k % kBlk;
+#pragma unroll
+            for (int ci = 0; ci < CH; ++ci) p[ci * kBlk] = acc[ci][q];
+        }
+    }
+}
+
+// dw[i] = sum over splits of part[s][i].  A workgroup owns 64 float4 outputs; its 16 wavefronts each
+// add the splits s = w, w+16, ... (in that order) and wavefront 0 adds the 16 sums in wavefront
+// order: a fixed tree, so the result does not depend on timing.  Layers with few filter elements
+// and many splits (1x1, 64 x 64) would otherwise leave the sum to a handful of threads.
+// dw may be the first partial itself (every element is read by the thread that later writes it).
+__global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, float4 *dw, size_t n4, int splits)
+{
+    __shared__ float4 red[16][64];
+    const int o = threadIdx.x % 64, sl = threadIdx.x / 64;
+    const size_t i = (size_t)blockIdx.x * 64 + o;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n4)
+        for (int p = sl; p < splits; p += 16) {
+            const float4 v = part[(size_t)p * n4 + i];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+    red[sl][o] = s;
+    __syncthreads();
+    if (sl == 0 && i < n4) {
+        const int lanes = splits < 16 ? splits : 16;
+        for (int q = 1; q < lanes; ++q) {
+            const float4 v = red[q][o];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        dw[i] = s;
+    }
+}
+
+// Run with the operand roles swapped (BWW that tests dy): the summed partials hold
+// dw'[c][k][S-1-v][R-1-u] in the filter layout of a layer with C and K exchanged; this kernel
+// writes dw[k][c][v][u] in the library layout.
 __global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__restrict__ part,
                                                                  float *__restrict__ dw, int K, int C, int S,
-                                                                 int R, int splits)
+                                                                 int R)
 {
     // one workgroup per 16x16 block (k block, c block, tap) of dw: the source block [ki][ci] is read
-    // row by row (coalesced) and summed over the splits, then written transposed through LDS
+    // row by row (coalesced), then written transposed through LDS
     __shared__ float tile[kBlk][kBlk + 1];
-    const size_t total = (size_t)K * C * S * R;
     int t = blockIdx.x;
     const int u = t % R; t /= R;
     const int v = t % S; t /= S;
@@ -352,9 +583,7 @@ __global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__
     const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
     const size_t src = ((((size_t)cb * (K / kBlk) + kb) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) +
                        a * kBlk + b;                                       // element [ki = a][ci = b]
-    float sum = part[src];
-    for (int p = 1; p < splits; ++p) sum += part[(size_t)p * total + src];
-    tile[a][b] = sum;
+    tile[a][b] = part[src];
     __syncthreads();
     dw[((((size_t)kb * (C / kBlk) + cb) * S + v) * R + u) * (kBlk * kBlk) + a * kBlk + b] = tile[b][a];   // [ci = a][ki = b]
 }
@@ -388,6 +617,27 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
     return A;
 }
 
+// 1x1 layers: chunks of kPwP pixels numbered across the minibatch; kw / cw = channels per workgroup
+BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw)
+{
+    BwwArgs A;
+    A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W; A.OH = d.H; A.OW = d.W; A.pw = 0; A.ph = 0;
+    A.tiles_h = A.tiles_w = 1;
+    const long long chunks = ((long long)d.N * d.H * d.W + kPwP - 1) / kPwP;
+    A.units = (int)chunks;                          // bww_fast_supported bounds N*H*W
+    A.cgroups = ceil_div(d.C, cw);
+    const int groups = ceil_div(d.K, kw) * A.cgroups;
+    const char *env = getenv("ST_BWW_WGS");
+    const int target = env ? atoi(env) : 512;
+    int splits = ceil_div(target > 0 ? target : 512, groups);
+    if (splits > A.units) splits = A.units;
+    if (splits < 1) splits = 1;
+    A.splits = splits;
+    return A;
+}
+
+int pw_kpl(const st_conv_desc &d) { return d.K % 256 == 0 ? 4 : (d.K % 128 == 0 ? 2 : 1); }
+
 size_t partial_bytes(const st_conv_desc &d, const BwwArgs &A)
 {
     if (A.splits == 1) return 0;
@@ -398,8 +648,24 @@ hipError_t reduce(const st_conv_desc &d, const BwwArgs &A, const float *part, fl
 {
     if (A.splits == 1) return hipSuccess;
     const size_t n4 = (size_t)d.K * d.C * d.S * d.R / 4;
-    hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((n4 + 63) / 64)), dim3(1024), 0, s,
                        reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(dw), n4, A.splits);
+    return hipGetLastError();
+}
+
+// exchanged roles: the partial sums (filter layout of the layer with C and K exchanged, taps reversed)
+// are first added in place into the first partial, which is then transposed into dw
+hipError_t reduce_swapped(const st_conv_desc &d, int splits, float *part, float *dw, hipStream_t s)
+{
+    const size_t total = (size_t)d.K * d.C * d.S * d.R;
+    if (splits > 1) {
+        hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((total / 4 + 63) / 64)), dim3(1024), 0, s,
+                           reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(part), total / 4, splits);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, part, dw, d.K, d.C,
+                       d.S, d.R);
     return hipGetLastError();
 }
 
@@ -433,20 +699,43 @@ bool bww_fast_supported(const st_conv_desc &d)
     const long long units = (long long)d.N * ceil_div(d.H + 2 * d.pad_h, 8) * ceil_div(d.W + 2 * d.pad_w, 16);
     if (units > 0x7fffffffLL) return false;
     if (d.R == 3 && d.S == 3) return d.pad_w <= 2 && d.pad_h <= 2;
-    if (d.R == 1 && d.S == 1) return d.pad_w == 0 && d.pad_h == 0;
+    if (d.R == 1 && d.S == 1)
+        return d.pad_w == 0 && d.pad_h == 0 && (long long)d.N * d.H * d.W / kPwP < 0x7fffff00LL;
     return false;
 }
 
 size_t bww_sparse_workspace(const st_conv_desc &d)
 {
+    if (d.R == 1 && d.S == 1) return partial_bytes(d, make_args_pw(d, 64 * pw_kpl(d), 64));
     return partial_bytes(d, make_args(d, kSparseTH, kSparseTW, true));       // same tiles for both strides
 }
 
 size_t bww_dense_workspace(const st_conv_desc &d)
 {
+    if (d.R == 1 && d.S == 1) return partial_bytes(d, make_args_pw(d, 128, 128));
     if (bww_s2(d)) return partial_bytes(d, make_args(d, kS2TH, kS2TW, false));
     return partial_bytes(d, make_args(d, kDenseTH, kDenseTW, false));
 }
+
+namespace {
+// e = the layer as the kernel sees it (e.C tested channels, e.K lane channels); swapped = dy tested:
+// the partial sums are then dw'[c][k] and go through the transposing reduction
+hipError_t launch_pw_sparse(const st_conv_desc &d, const st_conv_desc &e, const float *tested, const float *other,
+                            float *dw, float *ws, bool swapped, hipStream_t s)
+{
+    const int kpl = pw_kpl(e);
+    const BwwArgs A = make_args_pw(e, 64 * kpl, 64);
+    float *part = (A.splits == 1 && !swapped) ? dw : ws;
+    dim3 grid(A.splits, ceil_div(e.K, 64 * kpl) * A.cgroups);
+    if (kpl == 4) hipLaunchKernelGGL(pw_bww_sparse_kernel<4>, grid, dim3(512), 0, s, A, tested, other, part);
+    else if (kpl == 2) hipLaunchKernelGGL(pw_bww_sparse_kernel<2>, grid, dim3(512), 0, s, A, tested, other, part);
+    else hipLaunchKernelGGL(pw_bww_sparse_kernel<1>, grid, dim3(512), 0, s, A, tested, other, part);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    if (!swapped) return reduce(d, A, part, dw, s);
+    return reduce_swapped(d, A.splits, ws, dw, s);
+}
+}  // namespace
 
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                              float *ws, hipStream_t s)
@@ -459,10 +748,8 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A, ws, dw, s);
     }
-    if (d.R == 3)
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
-    else
-        hipLaunchKernelGGL((bww_sparse_kernel<1, 1, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
+    if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
@@ -493,6 +780,10 @@ bool bww_dy_fast_supported(const st_conv_desc &d)
 
 size_t bww_sparse_dy_workspace(const st_conv_desc &d)
 {
+    if (d.R == 1 && d.S == 1) {
+        const st_conv_desc e = swapped_desc(d);
+        return (size_t)make_args_pw(e, 64 * pw_kpl(e), 64).splits * d.K * d.C * sizeof(float);
+    }
     if (bww_s2(d)) return (size_t)make_args_s2_dy(d).splits * d.K * d.C * d.S * d.R * sizeof(float);
     const st_conv_desc e = swapped_desc(d);
     const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
@@ -508,24 +799,16 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
         hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, ws);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
-        const size_t total = (size_t)d.K * d.C * d.S * d.R;
-        hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, ws, dw,
-                           d.K, d.C, d.S, d.R, A.splits);
-        return hipGetLastError();
+        return reduce_swapped(d, A.splits, ws, dw, s);
     }
     const st_conv_desc e = swapped_desc(d);
+    if (d.R == 1) return launch_pw_sparse(d, e, dy, x, dw, ws, true, s);
     const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
     dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
-    if (d.R == 3)
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
-    else
-        hipLaunchKernelGGL((bww_sparse_kernel<1, 1, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    const size_t total = (size_t)d.K * d.C * d.S * d.R;
-    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, ws, dw,
-                       d.K, d.C, d.S, d.R, A.splits);
-    return hipGetLastError();
+    return reduce_swapped(d, A.splits, ws, dw, s);
 }
 
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
@@ -539,13 +822,17 @@ hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A2, ws, dw, s);
     }
+    if (d.R == 1) {
+        const BwwArgs A1 = make_args_pw(d, 128, 128);
+        dim3 grid1(A1.splits, ceil_div(d.K, 128) * A1.cgroups);
+        hipLaunchKernelGGL(pw_bww_dense_kernel, grid1, dim3(256), 0, s, A1, x, dy, A1.splits == 1 ? dw : ws);
+        hipError_t err = hipGetLastError();
+        return err != hipSuccess ? err : reduce(d, A1, ws, dw, s);
+    }
     const BwwArgs A = make_args(d, kDenseTH, kDenseTW, false);
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
-    if (d.R == 3)
-        hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), grid, dim3(256), 0, s, A, x, dy, part);
-    else
-        hipLaunchKernelGGL((bww_dense_kernel<1, 1, kDenseTH, kDenseTW>), grid, dim3(256), 0, s, A, x, dy, part);
+    hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), grid, dim3(256), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
