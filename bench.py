@@ -174,6 +174,7 @@ def main():
 
     ws = {(p, dn): ws_for(p, dn) for p in (0, 1, 2) for dn in (False, True)}
     ws_dy = ws_for(st.ST_PASS_BWW_DY, False)
+    ws_auto = ws_for(st.ST_PASS_BWW_AUTO, False)
 
     def run_pass(name, dense, xin=None, dyin=None):
         xin = xd if xin is None else xin
@@ -184,6 +185,8 @@ def main():
             (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(d, dyin, wd, dx, ws[1, dense], stream)
         elif name == "bww_dy":          # side measurement: BWW with the zero test on dy (not part of the step)
             st.st_conv_bww_dy(d, xin, dyin, dw, ws_dy, stream)
+        elif name == "bww_auto":        # side measurement: BWW that samples both operands and picks one
+            st.st_conv_bww_auto(d, xin, dyin, dw, ws_auto, stream)
         else:
             (st.st_conv_bww_dense if dense else st.st_conv_bww)(d, xin, dyin, dw, ws[2, dense], stream)
 
@@ -244,6 +247,7 @@ def main():
     dy_med, _ = time_pass("bww_dy", False, args.steps)
     passes["bww"]["tests_dy_ms"] = round(dy_med, 4)
     passes["bww"]["tests_dy_zero_fraction"] = round(pdy, 4)
+    passes["bww"]["auto_select_ms"] = round(time_pass("bww_auto", False, args.steps)[0], 4)
 
     # ---- roofline of the dominant kernel ----
     # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy), so the

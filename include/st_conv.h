@@ -69,7 +69,7 @@ typedef struct {
     int32_t pad_w, pad_h;       /* zeros added on each side of W / of H */
 } st_conv_desc;
 
-enum { ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2, ST_PASS_BWW_DY = 3 };
+enum { ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2, ST_PASS_BWW_DY = 3, ST_PASS_BWW_AUTO = 4 };
 
 /*
  * FWD, Eq. (1) of Sec. 2.1 (correlation, filter not flipped, no bias):
@@ -127,9 +127,21 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
                          void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * BWW that picks the tested operand itself, per call: Sec. 5.3 tests the operand with the higher
+ * average sparsity, and Sec. 5.4 names the fixed choice a limitation.  A first kernel counts the
+ * zeros in a sample of x and of dy (one block of 1024 elements in eight); then both forms above are
+ * enqueued, and the one the counts do not select returns at once: x is tested unless dy has the
+ * strictly larger zero fraction.  Same tensors, same result, no host synchronisation; the cost is
+ * the sampling pass (about 1/8 of x and dy is read once more) and one empty launch.
+ * Workspace: st_conv_workspace_bytes(desc, ST_PASS_BWW_AUTO, 0).
+ */
+st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Bytes of device workspace the given pass needs for this geometry
  * (pass = ST_PASS_*, dense = 0 for st_conv_<pass>, 1 for st_conv_<pass>_dense; ST_PASS_BWW_DY with
- * dense = 0 is st_conv_bww_dy).
+ * dense = 0 is st_conv_bww_dy, ST_PASS_BWW_AUTO with dense = 0 is st_conv_bww_auto).
  * Returns 0 when none is needed or when desc is invalid (the pass itself then
  * reports the error).  The workspace must be 256-byte aligned.  Its contents
  * need not be initialised and are undefined afterwards; two calls that are in

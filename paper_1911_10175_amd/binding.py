@@ -10,13 +10,13 @@ import ctypes
 import os
 from dataclasses import dataclass
 
-ST_PASS_FWD, ST_PASS_BWI, ST_PASS_BWW, ST_PASS_BWW_DY = 0, 1, 2, 3
+ST_PASS_FWD, ST_PASS_BWI, ST_PASS_BWW, ST_PASS_BWW_DY, ST_PASS_BWW_AUTO = 0, 1, 2, 3, 4
 ST_OK = 0
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libst_conv.so"
 EXPORTS = ("st_conv_fwd", "st_conv_fwd_dense", "st_conv_bwi", "st_conv_bwi_dense", "st_conv_bww",
-           "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_workspace_bytes", "st_status_str", "st_conv_version")
+           "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_workspace_bytes", "st_status_str", "st_conv_version")
 
 
 class StConvError(RuntimeError):
@@ -80,7 +80,7 @@ def load_library():
                 f"or make -C paper_1911_10175_amd/csrc).  There is no fallback path.")
         lib = ctypes.CDLL(path)
         p = ctypes.c_void_p
-        for name in EXPORTS[:7]:
+        for name in EXPORTS[:8]:
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.POINTER(_CDesc), p, p, p, p, ctypes.c_size_t, p]
             fn.restype = ctypes.c_int
@@ -167,3 +167,7 @@ def st_conv_bww_dense(desc, x, dy, dw, ws=None, stream=None, ws_bytes=None, chec
 
 def st_conv_bww_dy(desc, x, dy, dw, ws=None, stream=None, ws_bytes=None, check=True):
     return _call("st_conv_bww_dy", desc, x, dy, dw, ws, ws_bytes, stream, check)
+
+
+def st_conv_bww_auto(desc, x, dy, dw, ws=None, stream=None, ws_bytes=None, check=True):
+    return _call("st_conv_bww_auto", desc, x, dy, dw, ws, ws_bytes, stream, check)

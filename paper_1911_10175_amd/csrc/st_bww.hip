@@ -41,7 +41,20 @@ struct BwwArgs {
     int units;                 // N * tiles_h * tiles_w
     int splits;                // partial sums; gridDim.x
     int cgroups;               // ceil(C/64)
+    // operand selection on the device (st_conv_bww_auto): when sel is set, the launch does nothing
+    // unless the sampled zero counts pick the operand this launch tests (want: 0 = x, 1 = dy)
+    const unsigned *sel;
+    int want;
 };
+
+// sel = {zeros of x in the sample, sample size of x, zeros of dy, sample size of dy}; dy is chosen
+// when its zero fraction is strictly larger
+__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
+{
+    if (!sel) return false;
+    const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
+    return (dy_sparser ? 1 : 0) != want;
+}
 
 // PSTEP = stride of the layer (1 or 2): positions of the halo between neighbouring tile pixels
 template <int R, int S, int TH, int TW, int PSTEP = 1>
@@ -97,6 +110,7 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
                                                             float *__restrict__ part)
 {
     using Cfg = BwwSparseCfg<R, S, TH, TW, MODE>;
+    if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
     constexpr int CH = 8;                 // input channels per wavefront
     constexpr int GP = Cfg::GP;           // pixels per group
@@ -433,6 +447,7 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
                                                                float *__restrict__ part)
 {
     constexpr int P = kPwP, CH = 8, GP = 4, KW = 64 * KPL;
+    if (deselected(A.sel, A.want)) return;
     __shared__ __attribute__((aligned(16))) float dyT[P * KW];
     __shared__ __attribute__((aligned(16))) float xT[P * 64];
 
@@ -542,8 +557,10 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
 // order: a fixed tree, so the result does not depend on timing.  Layers with few filter elements
 // and many splits (1x1, 64 x 64) would otherwise leave the sum to a handful of threads.
 // dw may be the first partial itself (every element is read by the thread that later writes it).
-__global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, float4 *dw, size_t n4, int splits)
+__global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, float4 *dw, size_t n4, int splits,
+                                                          const unsigned *sel, int want)
 {
+    if (deselected(sel, want)) return;
     __shared__ float4 red[16][64];
     const int o = threadIdx.x % 64, sl = threadIdx.x / 64;
     const size_t i = (size_t)blockIdx.x * 64 + o;
@@ -570,8 +587,9 @@ __global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, fl
 // writes dw[k][c][v][u] in the library layout.
 __global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__restrict__ part,
                                                                  float *__restrict__ dw, int K, int C, int S,
-                                                                 int R)
+                                                                 int R, const unsigned *sel)
 {
+    if (deselected(sel, 1)) return;
     // one workgroup per 16x16 block (k block, c block, tap) of dw: the source block [ki][ci] is read
     // row by row (coalesced), then written transposed through LDS
     __shared__ float tile[kBlk][kBlk + 1];
@@ -596,6 +614,7 @@ constexpr int kS2TH = 4, kS2TW = 8;
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 {
     BwwArgs A;
+    A.sel = nullptr; A.want = 0;
     A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W;
     A.OH = (d.H + 2 * d.pad_h - d.S) / d.stride_h + 1;
     A.OW = (d.W + 2 * d.pad_w - d.R) / d.stride_w + 1;
@@ -621,6 +640,7 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw)
 {
     BwwArgs A;
+    A.sel = nullptr; A.want = 0;
     A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W; A.OH = d.H; A.OW = d.W; A.pw = 0; A.ph = 0;
     A.tiles_h = A.tiles_w = 1;
     const long long chunks = ((long long)d.N * d.H * d.W + kPwP - 1) / kPwP;
@@ -646,26 +666,29 @@ size_t partial_bytes(const st_conv_desc &d, const BwwArgs &A)
 
 hipError_t reduce(const st_conv_desc &d, const BwwArgs &A, const float *part, float *dw, hipStream_t s)
 {
-    if (A.splits == 1) return hipSuccess;
+    if (A.splits == 1) return hipSuccess;               // the kernel wrote dw itself
     const size_t n4 = (size_t)d.K * d.C * d.S * d.R / 4;
     hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((n4 + 63) / 64)), dim3(1024), 0, s,
-                       reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(dw), n4, A.splits);
+                       reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(dw), n4, A.splits, A.sel,
+                       A.want);
     return hipGetLastError();
 }
 
 // exchanged roles: the partial sums (filter layout of the layer with C and K exchanged, taps reversed)
 // are first added in place into the first partial, which is then transposed into dw
-hipError_t reduce_swapped(const st_conv_desc &d, int splits, float *part, float *dw, hipStream_t s)
+hipError_t reduce_swapped(const st_conv_desc &d, int splits, float *part, float *dw, hipStream_t s,
+                          const unsigned *sel)
 {
     const size_t total = (size_t)d.K * d.C * d.S * d.R;
     if (splits > 1) {
         hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((total / 4 + 63) / 64)), dim3(1024), 0, s,
-                           reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(part), total / 4, splits);
+                           reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(part), total / 4, splits,
+                           sel, 1);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, part, dw, d.K, d.C,
-                       d.S, d.R);
+                       d.S, d.R, sel);
     return hipGetLastError();
 }
 
@@ -721,10 +744,11 @@ namespace {
 // e = the layer as the kernel sees it (e.C tested channels, e.K lane channels); swapped = dy tested:
 // the partial sums are then dw'[c][k] and go through the transposing reduction
 hipError_t launch_pw_sparse(const st_conv_desc &d, const st_conv_desc &e, const float *tested, const float *other,
-                            float *dw, float *ws, bool swapped, hipStream_t s)
+                            float *dw, float *ws, bool swapped, hipStream_t s, const unsigned *sel)
 {
     const int kpl = pw_kpl(e);
-    const BwwArgs A = make_args_pw(e, 64 * kpl, 64);
+    BwwArgs A = make_args_pw(e, 64 * kpl, 64);
+    A.sel = sel; A.want = swapped ? 1 : 0;
     float *part = (A.splits == 1 && !swapped) ? dw : ws;
     dim3 grid(A.splits, ceil_div(e.K, 64 * kpl) * A.cgroups);
     if (kpl == 4) hipLaunchKernelGGL(pw_bww_sparse_kernel<4>, grid, dim3(512), 0, s, A, tested, other, part);
@@ -733,14 +757,15 @@ hipError_t launch_pw_sparse(const st_conv_desc &d, const st_conv_desc &e, const 
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (!swapped) return reduce(d, A, part, dw, s);
-    return reduce_swapped(d, A.splits, ws, dw, s);
+    return reduce_swapped(d, A.splits, ws, dw, s, sel);
 }
 }  // namespace
 
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                             float *ws, hipStream_t s)
+                             float *ws, hipStream_t s, const unsigned *sel)
 {
-    const BwwArgs A = make_args(d, kSparseTH, kSparseTW, true);
+    BwwArgs A = make_args(d, kSparseTH, kSparseTW, true);
+    A.sel = sel; A.want = 0;
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
     if (bww_s2(d)) {
@@ -748,7 +773,7 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A, ws, dw, s);
     }
-    if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s);
+    if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s, sel);
     hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -791,24 +816,26 @@ size_t bww_sparse_dy_workspace(const st_conv_desc &d)
 }
 
 hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                                float *ws, hipStream_t s)
+                                float *ws, hipStream_t s, const unsigned *sel)
 {
     if (bww_s2(d)) {
-        const BwwArgs A = make_args_s2_dy(d);
+        BwwArgs A = make_args_s2_dy(d);
+        A.sel = sel; A.want = 1;
         dim3 grid(A.splits, ceil_div(A.K, 64) * A.cgroups);
         hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, ws);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
-        return reduce_swapped(d, A.splits, ws, dw, s);
+        return reduce_swapped(d, A.splits, ws, dw, s, sel);
     }
     const st_conv_desc e = swapped_desc(d);
-    if (d.R == 1) return launch_pw_sparse(d, e, dy, x, dw, ws, true, s);
-    const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
+    if (d.R == 1) return launch_pw_sparse(d, e, dy, x, dw, ws, true, s, sel);
+    BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
+    A.sel = sel; A.want = 1;
     dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
     hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    return reduce_swapped(d, A.splits, ws, dw, s);
+    return reduce_swapped(d, A.splits, ws, dw, s, sel);
 }
 
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,

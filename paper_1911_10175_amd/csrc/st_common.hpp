@@ -36,10 +36,15 @@ hipError_t launch_generic_fwd(const st_conv_desc &d, const float *x, const float
                               bool sparse, hipStream_t s);
 hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const float *w, float *dx,
                               bool sparse, hipStream_t s);
+// sel (here and below): device counters of launch_zero_sample; when set, the launch is a no-op unless
+// they select the operand it tests (x unless dy has the strictly larger zero fraction)
 hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                              bool sparse, hipStream_t s);
+                              bool sparse, hipStream_t s, const unsigned *sel = nullptr);
 hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                                 hipStream_t s);
+                                 hipStream_t s, const unsigned *sel = nullptr);
+// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of one block in eight)
+hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
+                              hipStream_t s);
 
 // filter transposition for stride-1 BWI: wt[C/16][K/16][S][R][16 k][16 c] with taps reversed
 hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s);
@@ -59,12 +64,12 @@ hipError_t launch_pw_dense(const Geom &g, const float *in, const float *wd, floa
 bool bww_fast_supported(const st_conv_desc &d);
 size_t bww_sparse_workspace(const st_conv_desc &d);
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                             float *ws, hipStream_t s);
+                             float *ws, hipStream_t s, const unsigned *sel = nullptr);
 // BWW that tests dy instead of x (operand roles exchanged, transposing final sum)
 bool bww_dy_fast_supported(const st_conv_desc &d);
 size_t bww_sparse_dy_workspace(const st_conv_desc &d);
 hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                                float *ws, hipStream_t s);
+                                float *ws, hipStream_t s, const unsigned *sel = nullptr);
 size_t bww_dense_workspace(const st_conv_desc &d);
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                             float *ws, hipStream_t s);

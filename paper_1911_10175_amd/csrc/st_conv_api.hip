@@ -67,6 +67,8 @@ bool ws_ok(const void *ws, size_t have, size_t need)
 
 st_status dev(hipError_t e) { return e == hipSuccess ? ST_OK : ST_ERR_DEVICE; }
 
+constexpr size_t kCounterBytes = 256;
+
 size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dense)
 {
     switch (pass) {
@@ -86,6 +88,12 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
     case ST_PASS_BWW_DY:
         if (dense) return workspace_bytes(d, o, ST_PASS_BWW, true);
         return st::bww_dy_fast_supported(d) ? st::bww_sparse_dy_workspace(d) : 0;
+    case ST_PASS_BWW_AUTO: {
+        if (dense) return workspace_bytes(d, o, ST_PASS_BWW, true);
+        // 256 bytes of counters, then the partial sums of whichever form runs
+        const size_t a = workspace_bytes(d, o, ST_PASS_BWW, false), b = workspace_bytes(d, o, ST_PASS_BWW_DY, false);
+        return kCounterBytes + (a > b ? a : b);
+    }
     default:
         return 0;
     }
@@ -164,6 +172,30 @@ st_status run_bww_dy(const st_conv_desc *d, const float *x, const float *dy, flo
     return dev(st::launch_bww_sparse_dy(*d, x, dy, dw, static_cast<float *>(ws), s));
 }
 
+// Both forms are enqueued; each starts by reading the sampled zero counts and returns at once unless
+// they select it, so exactly one of them computes dw.  No host synchronisation is involved.
+st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
+                       size_t ws_bytes, void *stream)
+{
+    Dims o;
+    st_status rc = validate(d, &o);
+    if (rc != ST_OK) return rc;
+    if (!x || !dy || !dw) return ST_ERR_NULL;
+    if ((long long)d->K * d->S * d->R > 0x7fffffffLL) return ST_ERR_UNSUPPORTED;
+    if (!ws_ok(ws, ws_bytes, workspace_bytes(*d, o, ST_PASS_BWW_AUTO, false))) return ST_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned *sel = static_cast<unsigned *>(ws);
+    float *part = reinterpret_cast<float *>(static_cast<char *>(ws) + kCounterBytes);
+    const size_t nx = (size_t)d->N * d->C * d->H * d->W, ny = (size_t)d->N * d->K * o.OH * o.OW;
+    if (st::launch_zero_sample(x, nx, dy, ny, sel, s) != hipSuccess) return ST_ERR_DEVICE;
+    hipError_t e = st::bww_fast_supported(*d) ? st::launch_bww_sparse(*d, x, dy, dw, part, s, sel)
+                                              : st::launch_generic_bww(*d, x, dy, dw, true, s, sel);
+    if (e != hipSuccess) return ST_ERR_DEVICE;
+    e = st::bww_dy_fast_supported(*d) ? st::launch_bww_sparse_dy(*d, x, dy, dw, part, s, sel)
+                                      : st::launch_generic_bww_dy(*d, x, dy, dw, s, sel);
+    return dev(e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -204,6 +236,12 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
     return run_bww_dy(desc, x, dy, dw, ws, ws_bytes, hip_stream);
 }
 
+st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float *dy, float *dw, void *ws,
+                           size_t ws_bytes, void *hip_stream)
+{
+    return run_bww_auto(desc, x, dy, dw, ws, ws_bytes, hip_stream);
+}
+
 st_status st_conv_bww_dense(const st_conv_desc *desc, const float *x, const float *dy, float *dw,
                             void *ws, size_t ws_bytes, void *hip_stream)
 {
@@ -230,6 +268,6 @@ const char *st_status_str(st_status status)
     }
 }
 
-const char *st_conv_version(void) { return "0.2"; }
+const char *st_conv_version(void) { return "0.3"; }
 
 }  // extern "C"

@@ -95,12 +95,20 @@ __global__ __launch_bounds__(64) void generic_bwi_kernel(st_conv_desc d, int OH,
 }
 
 // dw[k,c,v,u] for k = 64*blockIdx.y + lane, (c,v,u) from blockIdx.x
+__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
+{
+    if (!sel) return false;
+    const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
+    return (dy_sparser ? 1 : 0) != want;
+}
+
 template <bool SPARSE>
 __global__ __launch_bounds__(64) void generic_bww_kernel(st_conv_desc d, int OH, int OW,
                                                          const float *__restrict__ x,
                                                          const float *__restrict__ dy,
-                                                         float *__restrict__ dw)
+                                                         float *__restrict__ dw, const unsigned *sel)
 {
+    if (deselected(sel, 0)) return;
     const int lane = threadIdx.x;
     const int k = blockIdx.y * kWave + lane;
     int t = blockIdx.x;
@@ -131,8 +139,9 @@ __global__ __launch_bounds__(64) void generic_bww_kernel(st_conv_desc d, int OH,
 __global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int OH, int OW,
                                                             const float *__restrict__ x,
                                                             const float *__restrict__ dy,
-                                                            float *__restrict__ dw)
+                                                            float *__restrict__ dw, const unsigned *sel)
 {
+    if (deselected(sel, 1)) return;
     const int lane = threadIdx.x;
     const int c = blockIdx.y * kWave + lane;
     int t = blockIdx.x;
@@ -157,6 +166,38 @@ __global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int 
             }
         }
     if (active) dw[flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk + ki] = acc;
+}
+
+// Zero statistics for the operand choice of BWW (SparseTrain Sec. 5.3 picks the operand with the
+// higher average sparsity): counts the elements equal to zero in a sample of a tensor, one block of
+// 1024 consecutive floats out of every `stride` blocks, and adds {zeros, elements looked at} to
+// out[0], out[1] with integer atomics (order-independent, hence deterministic).
+__global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restrict__ t, size_t n, unsigned stride,
+                                                          unsigned *__restrict__ out)
+{
+    const size_t base = (size_t)blockIdx.x * stride * 1024 + threadIdx.x * 4;
+    unsigned zeros = 0, seen = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (base + j < n) {
+            zeros += t[base + j] == 0.f ? 1u : 0u;
+            seen += 1u;
+        }
+    // wavefront sums, then one atomic per wavefront
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        zeros += __shfl_down(zeros, off);
+        seen += __shfl_down(seen, off);
+    }
+    if (threadIdx.x % kWave == 0 && seen) {
+        atomicAdd(out, zeros);
+        atomicAdd(out + 1, seen);
+    }
+}
+
+__global__ void clear_counters_kernel(unsigned *c)
+{
+    c[threadIdx.x] = 0u;
 }
 
 // wt[cb][kb][S-1-v][R-1-u][ki][ci] = w[kb][cb][v][u][ci][ki]
@@ -212,25 +253,43 @@ hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const floa
 }
 
 hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                              bool sparse, hipStream_t s)
+                              bool sparse, hipStream_t s, const unsigned *sel)
 {
     int OH, OW;
     out_dims(d, OH, OW);
     dim3 grid(d.C * d.S * d.R, ceil_div(d.K, kWave), 1);
     if (sparse)
-        hipLaunchKernelGGL(generic_bww_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
+        hipLaunchKernelGGL(generic_bww_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw, sel);
     else
-        hipLaunchKernelGGL(generic_bww_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
+        hipLaunchKernelGGL(generic_bww_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw, sel);
     return hipGetLastError();
 }
 
 hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                                 hipStream_t s)
+                                 hipStream_t s, const unsigned *sel)
 {
     int OH, OW;
     out_dims(d, OH, OW);
     dim3 grid(d.K * d.S * d.R, ceil_div(d.C, kWave), 1);
-    hipLaunchKernelGGL(generic_bww_dy_kernel, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw);
+    hipLaunchKernelGGL(generic_bww_dy_kernel, grid, dim3(64), 0, s, d, OH, OW, x, dy, dw, sel);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
+                              hipStream_t s)
+{
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(4), 0, s, counters);
+    const float *t[2] = {x, dy};
+    const size_t n[2] = {nx, ny};
+    for (int i = 0; i < 2; ++i) {
+        const size_t blocks = (n[i] + 1023) / 1024;
+        // every 8th block; fewer for huge tensors (the 32-bit counters hold at most 2^30 sampled
+        // elements), all of them for small ones
+        size_t stride = blocks < 64 ? 1 : 8;
+        while ((blocks + stride - 1) / stride > (1u << 20)) stride *= 2;
+        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)((blocks + stride - 1) / stride)), dim3(256), 0, s, t[i],
+                           n[i], (unsigned)stride, counters + 2 * i);
+    }
     return hipGetLastError();
 }
 

@@ -60,12 +60,16 @@ class DeviceLayer:
         return st.unpack_activations(dx.cpu().numpy())
 
     def bww(self, dense=False):
-        """dense = False: st_conv_bww (tests x); True: st_conv_bww_dense; "dy": st_conv_bww_dy."""
+        """dense = False: st_conv_bww (tests x); True: st_conv_bww_dense; "dy": st_conv_bww_dy;
+        "auto": st_conv_bww_auto (its workspace is kept in self.auto_ws for inspection)."""
         g = self.g
         dw = nan_like((g.K // 16, g.C // 16, g.S, g.R, 16, 16))
         if dense == "dy":
             ws = workspace(self.d, st.ST_PASS_BWW_DY, False)
             st.st_conv_bww_dy(self.d, self.x, self.dy, dw, ws)
+        elif dense == "auto":
+            ws = self.auto_ws = workspace(self.d, st.ST_PASS_BWW_AUTO, False)
+            st.st_conv_bww_auto(self.d, self.x, self.dy, dw, ws)
         else:
             ws = workspace(self.d, st.ST_PASS_BWW, dense)
             (st.st_conv_bww_dense if dense else st.st_conv_bww)(self.d, self.x, self.dy, dw, ws)
@@ -74,8 +78,9 @@ class DeviceLayer:
 
 
 def bww_variants(variants):
-    """The BWW entry points to check: the dy-testing one rides along with the x-testing one."""
-    return tuple(variants) + (("dy",) if False in variants else ())
+    """The BWW entry points to check: the dy-testing and the self-selecting one ride along with the
+    x-testing one."""
+    return tuple(variants) + (("dy", "auto") if False in variants else ())
 
 
 def assert_close(got, ref, ref_abs, what):

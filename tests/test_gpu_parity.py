@@ -184,6 +184,41 @@ def test_stride2_degenerate_sparsity():
         check_all_passes_full(g, x, w, dy, f"s2 p={p}")
 
 
+def sampled_zero_counts(packed: np.ndarray):
+    """The library's sampling recipe, restated: blocks of 1024 consecutive floats, every 8th block
+    (all blocks when there are fewer than 64)."""
+    flat = packed.reshape(-1)
+    blocks = (flat.size + 1023) // 1024
+    stride = 1 if blocks < 64 else 8
+    zeros = seen = 0
+    for b in range(0, blocks, stride):
+        chunk = flat[b * 1024:(b + 1) * 1024]
+        zeros += int((chunk == 0).sum())
+        seen += chunk.size
+    return zeros, seen
+
+
+@pytest.mark.parametrize("px,pdy", [(0.2, 0.8), (0.8, 0.2), (0.0, 0.0)])
+@pytest.mark.parametrize("g", [Geom(2, 64, 128, 24, 24, 3, 3, 1, 1, 1, 1), Geom(4, 128, 64, 14, 14, 1, 1),
+                               Geom(2, 32, 32, 16, 16, 3, 3, 2, 2, 1, 1), Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2)],
+                         ids=["3x3", "1x1", "3x3s2", "5x5generic"])
+def test_bww_auto_selects_the_sparser_operand(g, px, pdy):
+    """st_conv_bww_auto: parity, and the zero counts it bases its choice on (Sec. 5.3 policy)."""
+    x, w, dy = synth(g, px, pdy, seed=51)
+    L = DeviceLayer(g, x, None, dy)
+    ref, ref_abs = st_ref.conv_bww(g, x, dy)
+    got = L.bww("auto")
+    assert_close(got, ref, ref_abs, f"BWW auto px={px} pdy={pdy}")
+    counters = L.auto_ws[:4].cpu().numpy().view(np.uint32)
+    zx, nx = sampled_zero_counts(st.pack_activations(x))
+    zdy, ndy = sampled_zero_counts(st.pack_activations(dy))
+    assert tuple(int(c) for c in counters) == (zx, nx, zdy, ndy)
+    # the sample agrees with the tensors' true zero fractions about which operand is sparser
+    if px != pdy:
+        assert (zdy * nx > zx * ndy) == (pdy > px)
+    assert np.array_equal(got, L.bww("auto")), "two runs differ"
+
+
 def test_config3_resnet3_2_full():
     """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
     L = stgen.RESNET3_2
