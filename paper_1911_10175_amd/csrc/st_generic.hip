@@ -173,25 +173,34 @@ __global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int 
 // 1024 consecutive floats out of every `stride` blocks, and adds {zeros, elements looked at} to
 // out[0], out[1] with integer atomics (order-independent, hence deterministic).
 __global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restrict__ t, size_t n, unsigned stride,
-                                                          unsigned *__restrict__ out)
+                                                          size_t sampled_blocks, unsigned *__restrict__ out)
 {
-    const size_t base = (size_t)blockIdx.x * stride * 1024 + threadIdx.x * 4;
+    __shared__ unsigned wz[4], wn[4];
     unsigned zeros = 0, seen = 0;
+    for (size_t b = blockIdx.x; b < sampled_blocks; b += gridDim.x) {
+        const size_t base = b * stride * 1024 + threadIdx.x * 4;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (base + j < n) {
-            zeros += t[base + j] == 0.f ? 1u : 0u;
-            seen += 1u;
-        }
-    // wavefront sums, then one atomic per wavefront
+        for (int j = 0; j < 4; ++j)
+            if (base + j < n) {
+                zeros += t[base + j] == 0.f ? 1u : 0u;
+                seen += 1u;
+            }
+    }
+    // wavefront sums, workgroup sum, then one pair of atomics per workgroup (a few hundred in all:
+    // atomics to one address are serialised by the memory system)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         zeros += __shfl_down(zeros, off);
         seen += __shfl_down(seen, off);
     }
-    if (threadIdx.x % kWave == 0 && seen) {
-        atomicAdd(out, zeros);
-        atomicAdd(out + 1, seen);
+    if (threadIdx.x % kWave == 0) {
+        wz[threadIdx.x / kWave] = zeros;
+        wn[threadIdx.x / kWave] = seen;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        atomicAdd(out, wz[0] + wz[1] + wz[2] + wz[3]);
+        atomicAdd(out + 1, wn[0] + wn[1] + wn[2] + wn[3]);
     }
 }
 
@@ -287,8 +296,9 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
         // elements), all of them for small ones
         size_t stride = blocks < 64 ? 1 : 8;
         while ((blocks + stride - 1) / stride > (1u << 20)) stride *= 2;
-        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)((blocks + stride - 1) / stride)), dim3(256), 0, s, t[i],
-                           n[i], (unsigned)stride, counters + 2 * i);
+        const size_t sampled = (blocks + stride - 1) / stride;
+        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 512 ? sampled : 512)), dim3(256), 0, s, t[i],
+                           n[i], (unsigned)stride, sampled, counters + 2 * i);
     }
     return hipGetLastError();
 }
