@@ -277,6 +277,19 @@ def test_config5_vgg_layers_full_batch_sampled(name, p):
     check_all_passes_sampled(g, x, w, dy, f"config5-{name}-p{p}", n_samples=2048, n_bww=128)
 
 
+TABLE1_REST = [l for l in stgen.table1_layers(32, 0.5, 0.6) if l.name.startswith("resnet") and
+               l.name not in ("resnet2_1b", "resnet2_2", "resnet2_3", "resnet3_2")]
+
+
+@pytest.mark.parametrize("layer", TABLE1_REST, ids=[l.name for l in TABLE1_REST])
+def test_table1_resnet_layers_full_batch_sampled(layer):
+    """The ResNet rows of Table 1 not covered above (the stride-2 layers and the late 1x1 layers
+    included) at N=32, all entry points, on sampled outputs."""
+    g = geom_of(layer)
+    x, w, dy = stgen.make_layer_tensors(layer, seed=6)
+    check_all_passes_sampled(g, x, w, dy, f"table1-{layer.name}", n_samples=2048, n_bww=128)
+
+
 def test_side_stream_and_reused_workspace():
     """Calls on a non-default stream with one workspace reused by consecutive calls give the same
     bits as calls on the default stream (the library only enqueues; it never synchronises)."""
