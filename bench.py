@@ -175,6 +175,7 @@ def main():
     ws = {(p, dn): ws_for(p, dn) for p in (0, 1, 2) for dn in (False, True)}
     ws_dy = ws_for(st.ST_PASS_BWW_DY, False)
     ws_auto = ws_for(st.ST_PASS_BWW_AUTO, False)
+    ws_fauto, ws_bauto = ws_for(st.ST_PASS_FWD_AUTO, False), ws_for(st.ST_PASS_BWI_AUTO, False)
 
     def run_pass(name, dense, xin=None, dyin=None):
         xin = xd if xin is None else xin
@@ -187,6 +188,10 @@ def main():
             st.st_conv_bww_dy(d, xin, dyin, dw, ws_dy, stream)
         elif name == "bww_auto":        # side measurement: BWW that samples both operands and picks one
             st.st_conv_bww_auto(d, xin, dyin, dw, ws_auto, stream)
+        elif name == "fwd_auto":        # side measurements: sparse/dense form picked on the device
+            st.st_conv_fwd_auto(d, xin, wd, y, ws_fauto, stream)
+        elif name == "bwi_auto":
+            st.st_conv_bwi_auto(d, dyin, wd, dx, ws_bauto, stream)
         else:
             (st.st_conv_bww_dense if dense else st.st_conv_bww)(d, xin, dyin, dw, ws[2, dense], stream)
 
@@ -248,6 +253,8 @@ def main():
     passes["bww"]["tests_dy_ms"] = round(dy_med, 4)
     passes["bww"]["tests_dy_zero_fraction"] = round(pdy, 4)
     passes["bww"]["auto_select_ms"] = round(time_pass("bww_auto", False, args.steps)[0], 4)
+    passes["fwd"]["auto_select_ms"] = round(time_pass("fwd_auto", False, args.steps)[0], 4)
+    passes["bwi"]["auto_select_ms"] = round(time_pass("bwi_auto", False, args.steps)[0], 4)
 
     # ---- roofline of the dominant kernel ----
     # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy), so the
@@ -282,6 +289,8 @@ def main():
                              "speedup": round(d_med / s_med, 3),
                              "effective_tflops": round(F / (s_med * 1e-3) / 1e12, 2)}
             row["bww"]["tests_dy_ms"] = round(time_pass("bww_dy", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
+            row["fwd"]["auto_select_ms"] = round(time_pass("fwd_auto", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
+            row["bwi"]["auto_select_ms"] = round(time_pass("bwi_auto", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
             sweep.append(row)
             del xs, dys
 

@@ -69,7 +69,10 @@ typedef struct {
     int32_t pad_w, pad_h;       /* zeros added on each side of W / of H */
 } st_conv_desc;
 
-enum { ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2, ST_PASS_BWW_DY = 3, ST_PASS_BWW_AUTO = 4 };
+enum {
+    ST_PASS_FWD = 0, ST_PASS_BWI = 1, ST_PASS_BWW = 2, ST_PASS_BWW_DY = 3, ST_PASS_BWW_AUTO = 4,
+    ST_PASS_FWD_AUTO = 5, ST_PASS_BWI_AUTO = 6
+};
 
 /*
  * FWD, Eq. (1) of Sec. 2.1 (correlation, filter not flipped, no bias):
@@ -139,9 +142,27 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
                            void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * FWD and BWI with the choice between the zero-skipping and the dense form made per call on the
+ * device.  Sec. 5.3 of the paper combines its kernels with the dense ones layer by layer, from
+ * profiled sparsity; here a first kernel counts the zeros in a sample of the tested operand (x for
+ * FWD, dy for BWI; one block of 1024 elements in eight), then both forms are enqueued and the one
+ * the count does not select returns at once.  The zero-skipping form runs when the sampled zero
+ * fraction reaches the break-even point measured for the geometry (40 % for 3x3 layers with K a
+ * multiple of 128, 62 % for narrower ones, 80 % / 60 % for FWD / BWI of stride-2 3x3 layers, 90 %
+ * for 1x1 layers with K a multiple of 256 and never for other 1x1 layers; always for geometries
+ * only the generic kernels cover).  Same tensors and layouts as st_conv_fwd / st_conv_bwi, same
+ * result to rounding, no host synchronisation.
+ * Workspace: st_conv_workspace_bytes(desc, ST_PASS_FWD_AUTO or ST_PASS_BWI_AUTO, 0).
+ */
+st_status st_conv_fwd_auto(const st_conv_desc *desc, const float *x, const float *w, float *y,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+st_status st_conv_bwi_auto(const st_conv_desc *desc, const float *dy, const float *w, float *dx,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Bytes of device workspace the given pass needs for this geometry
  * (pass = ST_PASS_*, dense = 0 for st_conv_<pass>, 1 for st_conv_<pass>_dense; ST_PASS_BWW_DY with
- * dense = 0 is st_conv_bww_dy, ST_PASS_BWW_AUTO with dense = 0 is st_conv_bww_auto).
+ * dense = 0 is st_conv_bww_dy, ST_PASS_*_AUTO with dense = 0 are the st_conv_*_auto entry points).
  * Returns 0 when none is needed or when desc is invalid (the pass itself then
  * reports the error).  The workspace must be 256-byte aligned.  Its contents
  * need not be initialised and are undefined afterwards; two calls that are in

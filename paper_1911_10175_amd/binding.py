@@ -11,12 +11,14 @@ import os
 from dataclasses import dataclass
 
 ST_PASS_FWD, ST_PASS_BWI, ST_PASS_BWW, ST_PASS_BWW_DY, ST_PASS_BWW_AUTO = 0, 1, 2, 3, 4
+ST_PASS_FWD_AUTO, ST_PASS_BWI_AUTO = 5, 6
 ST_OK = 0
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libst_conv.so"
 EXPORTS = ("st_conv_fwd", "st_conv_fwd_dense", "st_conv_bwi", "st_conv_bwi_dense", "st_conv_bww",
-           "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_workspace_bytes", "st_status_str", "st_conv_version")
+           "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_fwd_auto", "st_conv_bwi_auto",
+           "st_conv_workspace_bytes", "st_status_str", "st_conv_version")
 
 
 class StConvError(RuntimeError):
@@ -80,7 +82,7 @@ def load_library():
                 f"or make -C paper_1911_10175_amd/csrc).  There is no fallback path.")
         lib = ctypes.CDLL(path)
         p = ctypes.c_void_p
-        for name in EXPORTS[:8]:
+        for name in EXPORTS[:10]:
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.POINTER(_CDesc), p, p, p, p, ctypes.c_size_t, p]
             fn.restype = ctypes.c_int
@@ -171,3 +173,11 @@ def st_conv_bww_dy(desc, x, dy, dw, ws=None, stream=None, ws_bytes=None, check=T
 
 def st_conv_bww_auto(desc, x, dy, dw, ws=None, stream=None, ws_bytes=None, check=True):
     return _call("st_conv_bww_auto", desc, x, dy, dw, ws, ws_bytes, stream, check)
+
+
+def st_conv_fwd_auto(desc, x, w, y, ws=None, stream=None, ws_bytes=None, check=True):
+    return _call("st_conv_fwd_auto", desc, x, w, y, ws, ws_bytes, stream, check)
+
+
+def st_conv_bwi_auto(desc, dy, w, dx, ws=None, stream=None, ws_bytes=None, check=True):
+    return _call("st_conv_bwi_auto", desc, dy, w, dx, ws, ws_bytes, stream, check)

@@ -47,14 +47,6 @@ struct BwwArgs {
     int want;
 };
 
-// sel = {zeros of x in the sample, sample size of x, zeros of dy, sample size of dy}; dy is chosen
-// when its zero fraction is strictly larger
-__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
-{
-    if (!sel) return false;
-    const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
-    return (dy_sparser ? 1 : 0) != want;
-}
 
 // PSTEP = stride of the layer (1 or 2): positions of the halo between neighbouring tile pixels
 template <int R, int S, int TH, int TW, int PSTEP = 1>

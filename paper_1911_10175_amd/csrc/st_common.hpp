@@ -26,25 +26,53 @@ struct Geom {
     int pw, ph;          // padding
     int uw, uh;          // spacing of the input samples on the grid the taps slide over (1; 2 for the
                          // BWI of a stride-2 layer, whose dy is spread out with zeros in between)
+    // sparse/dense choice on the device (st_conv_fwd_auto, st_conv_bwi_auto): when sel is set the
+    // launch does nothing unless the sampled zero fraction of the tested operand, sel[0] / sel[1],
+    // selects this form: the zero-skipping one (want = 0) from thr per mille upwards, else the
+    // dense one (want = 1)
+    const unsigned *sel;
+    int want;
+    unsigned thr;
 };
+
+#if defined(__HIPCC__)
+__device__ __forceinline__ bool form_deselected(const unsigned *sel, int want, unsigned thr)
+{
+    if (!sel) return false;
+    const bool sparse = (unsigned long long)sel[0] * 1000ull >= (unsigned long long)thr * sel[1];
+    return (sparse ? 0 : 1) != want;
+}
+
+// BWW operand choice (st_conv_bww_auto): sel = {zeros of x in the sample, sample size of x, zeros of dy,
+// sample size of dy}; dy (want = 1) is tested when its zero fraction is strictly larger
+__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
+{
+    if (!sel) return false;
+    const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
+    return (dy_sparser ? 1 : 0) != want;
+}
+#endif
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---- launchers (each returns hipSuccess or the launch error) -------------------------------
 // generic kernels: any geometry the API accepts
 hipError_t launch_generic_fwd(const st_conv_desc &d, const float *x, const float *w, float *y,
-                              bool sparse, hipStream_t s);
+                              bool sparse, hipStream_t s, const unsigned *sel = nullptr, unsigned thr = 0);
 hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const float *w, float *dx,
-                              bool sparse, hipStream_t s);
+                              bool sparse, hipStream_t s, const unsigned *sel = nullptr, unsigned thr = 0);
 // sel (here and below): device counters of launch_zero_sample; when set, the launch is a no-op unless
 // they select the operand it tests (x unless dy has the strictly larger zero fraction)
 hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                               bool sparse, hipStream_t s, const unsigned *sel = nullptr);
 hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                                  hipStream_t s, const unsigned *sel = nullptr);
-// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of one block in eight)
+// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of one block in eight); dy may be null
 hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
                               hipStream_t s);
+// zero fraction (per mille) of the tested operand from which the zero-skipping FWD/BWI form beats the
+// dense one for this geometry (measured; 1001 = never)
+unsigned fwd_sparse_threshold(const Geom &g);
 
 // filter transposition for stride-1 BWI: wt[C/16][K/16][S][R][16 k][16 c] with taps reversed
 hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s);

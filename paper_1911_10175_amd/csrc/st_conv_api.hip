@@ -36,6 +36,7 @@ Geom fwd_geom(const st_conv_desc &d, const Dims &o)
     g.Hi = d.H; g.Wi = d.W; g.Ho = o.OH; g.Wo = o.OW;
     g.R = d.R; g.S = d.S; g.sw = d.stride_w; g.sh = d.stride_h; g.pw = d.pad_w; g.ph = d.pad_h;
     g.uw = 1; g.uh = 1;
+    g.sel = nullptr; g.want = 0; g.thr = 0;
     return g;
 }
 
@@ -51,6 +52,7 @@ bool bwi_as_fwd(const st_conv_desc &d, const Dims &o, Geom *g)
     g->R = d.R; g->S = d.S; g->sw = 1; g->sh = 1;
     g->uw = d.stride_w; g->uh = d.stride_h;
     g->pw = d.R - 1 - d.pad_w; g->ph = d.S - 1 - d.pad_h;
+    g->sel = nullptr; g->want = 0; g->thr = 0;
     return true;
 }
 
@@ -68,6 +70,8 @@ bool ws_ok(const void *ws, size_t have, size_t need)
 st_status dev(hipError_t e) { return e == hipSuccess ? ST_OK : ST_ERR_DEVICE; }
 
 constexpr size_t kCounterBytes = 256;
+
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
 size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dense)
 {
@@ -88,6 +92,13 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
     case ST_PASS_BWW_DY:
         if (dense) return workspace_bytes(d, o, ST_PASS_BWW, true);
         return st::bww_dy_fast_supported(d) ? st::bww_sparse_dy_workspace(d) : 0;
+    case ST_PASS_FWD_AUTO:
+    case ST_PASS_BWI_AUTO: {
+        // counters, then the workspaces of the zero-skipping and of the dense form side by side
+        const int base = pass == ST_PASS_FWD_AUTO ? ST_PASS_FWD : ST_PASS_BWI;
+        if (dense) return workspace_bytes(d, o, base, true);
+        return kCounterBytes + align256(workspace_bytes(d, o, base, false)) + workspace_bytes(d, o, base, true);
+    }
     case ST_PASS_BWW_AUTO: {
         if (dense) return workspace_bytes(d, o, ST_PASS_BWW, true);
         // 256 bytes of counters, then the partial sums of whichever form runs
@@ -172,6 +183,62 @@ st_status run_bww_dy(const st_conv_desc *d, const float *x, const float *dy, flo
     return dev(st::launch_bww_sparse_dy(*d, x, dy, dw, static_cast<float *>(ws), s));
 }
 
+// FWD (bwi = false) or BWI with the form chosen on the device: the zeros of a sample of the tested
+// operand are counted, then the zero-skipping and the dense form are both enqueued and the one the
+// count does not select returns at once (the filter copies of both are written regardless: they are
+// small).  SparseTrain Sec. 5.3 combines its kernels with the dense ones per layer from profiles;
+// this makes the same choice per call.
+st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float *w, float *out, void *ws,
+                           size_t ws_bytes, void *stream, bool bwi)
+{
+    Dims o;
+    st_status rc = validate(d, &o);
+    if (rc != ST_OK) return rc;
+    if (!act || !w || !out) return ST_ERR_NULL;
+    const int pass = bwi ? ST_PASS_BWI_AUTO : ST_PASS_FWD_AUTO, base = bwi ? ST_PASS_BWI : ST_PASS_FWD;
+    if (!ws_ok(ws, ws_bytes, workspace_bytes(*d, o, pass, false))) return ST_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned *sel = static_cast<unsigned *>(ws);
+    char *p = static_cast<char *>(ws) + kCounterBytes;
+    float *ws_sparse = reinterpret_cast<float *>(p);
+    float *ws_dense = reinterpret_cast<float *>(p + align256(workspace_bytes(*d, o, base, false)));
+    const size_t n_act = bwi ? (size_t)d->N * d->K * o.OH * o.OW : (size_t)d->N * d->C * d->H * d->W;
+    if (st::launch_zero_sample(act, n_act, nullptr, 0, sel, s) != hipSuccess) return ST_ERR_DEVICE;
+
+    Geom g = fwd_geom(*d, o);
+    const bool as_corr = bwi ? bwi_as_fwd(*d, o, &g) : true;
+    const bool fast_sparse = as_corr && st::fwd_sparse_supported(g);
+    const bool fast_dense = as_corr && st::fwd_dense_supported(g);
+    g.sel = sel;
+    g.thr = fast_sparse ? st::fwd_sparse_threshold(g) : 0;
+    if (!fast_dense && fast_sparse) g.thr = 0;      // tiled zero-skipping form against a generic dense one
+    hipError_t e;
+    // zero-skipping form
+    g.want = 0;
+    if (fast_sparse) {
+        const float *f = w;
+        if (bwi) {
+            if (st::launch_transpose_filters(*d, w, ws_sparse, s) != hipSuccess) return ST_ERR_DEVICE;
+            f = ws_sparse;
+        }
+        e = st::launch_fwd_sparse(g, act, f, out, s);
+    } else {
+        e = bwi ? st::launch_generic_bwi(*d, act, w, out, true, s, sel, g.thr)
+                : st::launch_generic_fwd(*d, act, w, out, true, s, sel, g.thr);
+    }
+    if (e != hipSuccess) return ST_ERR_DEVICE;
+    // dense form
+    g.want = 1;
+    if (fast_dense) {
+        if (st::launch_reformat_filters(g, bwi, w, ws_dense, s) != hipSuccess) return ST_ERR_DEVICE;
+        e = st::launch_fwd_dense(g, act, ws_dense, out, s);
+    } else {
+        e = bwi ? st::launch_generic_bwi(*d, act, w, out, false, s, sel, g.thr)
+                : st::launch_generic_fwd(*d, act, w, out, false, s, sel, g.thr);
+    }
+    return dev(e);
+}
+
 // Both forms are enqueued; each starts by reading the sampled zero counts and returns at once unless
 // they select it, so exactly one of them computes dw.  No host synchronisation is involved.
 st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
@@ -236,6 +303,18 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
     return run_bww_dy(desc, x, dy, dw, ws, ws_bytes, hip_stream);
 }
 
+st_status st_conv_fwd_auto(const st_conv_desc *desc, const float *x, const float *w, float *y, void *ws,
+                           size_t ws_bytes, void *hip_stream)
+{
+    return run_fwd_bwi_auto(desc, x, w, y, ws, ws_bytes, hip_stream, false);
+}
+
+st_status st_conv_bwi_auto(const st_conv_desc *desc, const float *dy, const float *w, float *dx, void *ws,
+                           size_t ws_bytes, void *hip_stream)
+{
+    return run_fwd_bwi_auto(desc, dy, w, dx, ws, ws_bytes, hip_stream, true);
+}
+
 st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float *dy, float *dw, void *ws,
                            size_t ws_bytes, void *hip_stream)
 {
@@ -268,6 +347,6 @@ const char *st_status_str(st_status status)
     }
 }
 
-const char *st_conv_version(void) { return "0.3"; }
+const char *st_conv_version(void) { return "0.4"; }
 
 }  // extern "C"

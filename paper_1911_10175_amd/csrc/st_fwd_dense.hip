@@ -66,6 +66,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
                                                            int tiles_h, int kgroups, int total_tiles)
 {
     using Cfg = FwdDenseCfg<R, S, TWD, MODE, PI, PJ>;
+    if (form_deselected(g.sel, g.want, g.thr)) return;
     constexpr int TH = Cfg::TH, TW = Cfg::TW, HW = Cfg::HW, HP = Cfg::HP, XST = Cfg::XST, BUF = Cfg::BUF;
     constexpr int TAPS = S * R, TQ = 4 / KQ, NPIX = Cfg::NPIX, NT = Cfg::NT, PSTEP = Cfg::PSTEP;
     constexpr int NLD = (HP * 4 + KQ * 64 - 1) / (KQ * 64);      // float4 loads per lane and block

@@ -66,6 +66,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
                                                                int slots_per_xcd)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
+    if (form_deselected(g.sel, g.want, g.thr)) return;          // uniform over the grid, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
     __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][kBlk * PST];
 
@@ -340,6 +341,19 @@ bool fwd_sparse_supported(const Geom &g)
     if (g.R == 3 && g.S == 3) return g.pw <= 2 && g.ph <= 2;
     if (g.R == 1 && g.S == 1) return g.pw == 0 && g.ph == 0;
     return false;
+}
+
+// Measured break-even points (profiles/config_table.md): the zero-skipping form needs 30-45 % zeros
+// with 128 output channels per wavefront and about 60 % with 64; the stride-2 FWD tests 2.25 taps
+// per element and its BWI is held by the filter stream of small tiles; a 1x1 layer saves K/64
+// multiply-adds per zero.
+unsigned fwd_sparse_threshold(const Geom &g)
+{
+    if (!fwd_sparse_supported(g)) return 0;         // generic kernels: the test only ever removes work
+    if (g.R == 1) return g.Ko % 256 == 0 ? 900 : 1001;
+    if (g.sw == 2) return 800;
+    if (g.uw == 2) return 600;
+    return g.Ko % 128 == 0 ? 400 : 620;
 }
 
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)

@@ -27,8 +27,9 @@ template <bool SPARSE>
 __global__ __launch_bounds__(64) void generic_fwd_kernel(st_conv_desc d, int OH, int OW,
                                                          const float *__restrict__ x,
                                                          const float *__restrict__ w,
-                                                         float *__restrict__ y)
+                                                         float *__restrict__ y, const unsigned *sel, unsigned thr)
 {
+    if (form_deselected(sel, SPARSE ? 0 : 1, thr)) return;
     const int lane = threadIdx.x;
     const int k = blockIdx.y * kWave + lane;
     const int ow = blockIdx.x % OW, oh = blockIdx.x / OW, n = blockIdx.z;
@@ -61,8 +62,9 @@ template <bool SPARSE>
 __global__ __launch_bounds__(64) void generic_bwi_kernel(st_conv_desc d, int OH, int OW,
                                                          const float *__restrict__ dy,
                                                          const float *__restrict__ w,
-                                                         float *__restrict__ dx)
+                                                         float *__restrict__ dx, const unsigned *sel, unsigned thr)
 {
+    if (form_deselected(sel, SPARSE ? 0 : 1, thr)) return;
     const int lane = threadIdx.x;
     const int c = blockIdx.y * kWave + lane;
     const int iw = blockIdx.x % d.W, ih = blockIdx.x / d.W, n = blockIdx.z;
@@ -95,13 +97,6 @@ __global__ __launch_bounds__(64) void generic_bwi_kernel(st_conv_desc d, int OH,
 }
 
 // dw[k,c,v,u] for k = 64*blockIdx.y + lane, (c,v,u) from blockIdx.x
-__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
-{
-    if (!sel) return false;
-    const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
-    return (dy_sparser ? 1 : 0) != want;
-}
-
 template <bool SPARSE>
 __global__ __launch_bounds__(64) void generic_bww_kernel(st_conv_desc d, int OH, int OW,
                                                          const float *__restrict__ x,
@@ -236,28 +231,28 @@ inline void out_dims(const st_conv_desc &d, int &OH, int &OW)
 }  // namespace
 
 hipError_t launch_generic_fwd(const st_conv_desc &d, const float *x, const float *w, float *y,
-                              bool sparse, hipStream_t s)
+                              bool sparse, hipStream_t s, const unsigned *sel, unsigned thr)
 {
     int OH, OW;
     out_dims(d, OH, OW);
     dim3 grid(OH * OW, ceil_div(d.K, kWave), d.N);
     if (sparse)
-        hipLaunchKernelGGL(generic_fwd_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, w, y);
+        hipLaunchKernelGGL(generic_fwd_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, x, w, y, sel, thr);
     else
-        hipLaunchKernelGGL(generic_fwd_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, w, y);
+        hipLaunchKernelGGL(generic_fwd_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, x, w, y, sel, thr);
     return hipGetLastError();
 }
 
 hipError_t launch_generic_bwi(const st_conv_desc &d, const float *dy, const float *w, float *dx,
-                              bool sparse, hipStream_t s)
+                              bool sparse, hipStream_t s, const unsigned *sel, unsigned thr)
 {
     int OH, OW;
     out_dims(d, OH, OW);
     dim3 grid(d.H * d.W, ceil_div(d.C, kWave), d.N);
     if (sparse)
-        hipLaunchKernelGGL(generic_bwi_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, dy, w, dx);
+        hipLaunchKernelGGL(generic_bwi_kernel<true>, grid, dim3(64), 0, s, d, OH, OW, dy, w, dx, sel, thr);
     else
-        hipLaunchKernelGGL(generic_bwi_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, dy, w, dx);
+        hipLaunchKernelGGL(generic_bwi_kernel<false>, grid, dim3(64), 0, s, d, OH, OW, dy, w, dx, sel, thr);
     return hipGetLastError();
 }
 
@@ -291,6 +286,7 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
     const float *t[2] = {x, dy};
     const size_t n[2] = {nx, ny};
     for (int i = 0; i < 2; ++i) {
+        if (!t[i]) continue;
         const size_t blocks = (n[i] + 1023) / 1024;
         // every 8th block; fewer for huge tensors (the 32-bit counters hold at most 2^30 sampled
         // elements), all of them for small ones

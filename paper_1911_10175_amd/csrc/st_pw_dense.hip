@@ -41,8 +41,10 @@ template <int PB, int KB, int DEPTH>
 __global__ __launch_bounds__(256) void pw_dense_kernel(int total_px, int HW, int CiB, int KoB,
                                                        const float *__restrict__ in,
                                                        const float *__restrict__ wd,
-                                                       float *__restrict__ out, int kgroups)
+                                                       float *__restrict__ out, int kgroups,
+                                                       const unsigned *sel, unsigned thr)
 {
+    if (form_deselected(sel, 1, thr)) return;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int l32 = lane % 32, half = lane / 32;
     // workgroup id -> (pixel group, channel group): the channel groups of one pixel group get ids that
@@ -163,7 +165,7 @@ hipError_t launch_pw(const Geom &g, const float *in, const float *wd, float *out
     const long long blocks = (pgroups + 7) / 8 * 8 * kgroups;
     if (blocks > 0x7fffffffLL || total_px > 0x7fffff00LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((pw_dense_kernel<PB, KB, DEPTH>), dim3((unsigned)blocks), dim3(256), 0, s, (int)total_px, HW,
-                       g.Ci / kBlk, g.Ko / kBlk, in, wd, out, kgroups);
+                       g.Ci / kBlk, g.Ko / kBlk, in, wd, out, kgroups, g.sel, g.thr);
     return hipGetLastError();
 }
 

@@ -44,18 +44,27 @@ class DeviceLayer:
         self.dy = dev(st.pack_activations(dy)) if dy is not None else None
 
     def fwd(self, dense=False):
+        """dense = False: st_conv_fwd; True: st_conv_fwd_dense; "auto": st_conv_fwd_auto."""
         g = self.g
         y = nan_like((g.N, g.K // 16, g.OH, g.OW, 16))
-        ws = workspace(self.d, st.ST_PASS_FWD, dense)
-        (st.st_conv_fwd_dense if dense else st.st_conv_fwd)(self.d, self.x, self.w, y, ws)
+        if dense == "auto":
+            ws = self.auto_ws = workspace(self.d, st.ST_PASS_FWD_AUTO, False)
+            st.st_conv_fwd_auto(self.d, self.x, self.w, y, ws)
+        else:
+            ws = workspace(self.d, st.ST_PASS_FWD, dense)
+            (st.st_conv_fwd_dense if dense else st.st_conv_fwd)(self.d, self.x, self.w, y, ws)
         torch.cuda.synchronize()
         return st.unpack_activations(y.cpu().numpy())
 
     def bwi(self, dense=False):
         g = self.g
         dx = nan_like((g.N, g.C // 16, g.H, g.W, 16))
-        ws = workspace(self.d, st.ST_PASS_BWI, dense)
-        (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(self.d, self.dy, self.w, dx, ws)
+        if dense == "auto":
+            ws = self.auto_ws = workspace(self.d, st.ST_PASS_BWI_AUTO, False)
+            st.st_conv_bwi_auto(self.d, self.dy, self.w, dx, ws)
+        else:
+            ws = workspace(self.d, st.ST_PASS_BWI, dense)
+            (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(self.d, self.dy, self.w, dx, ws)
         torch.cuda.synchronize()
         return st.unpack_activations(dx.cpu().numpy())
 
@@ -83,6 +92,11 @@ def bww_variants(variants):
     return tuple(variants) + (("dy", "auto") if False in variants else ())
 
 
+def fwd_variants(variants):
+    """FWD / BWI entry points to check: the self-selecting one rides along when both forms are checked."""
+    return tuple(variants) + (("auto",) if False in variants and True in variants else ())
+
+
 def assert_close(got, ref, ref_abs, what):
     assert got.shape == ref.shape, what
     assert np.isfinite(got).all(), f"{what}: non-finite or unwritten output elements"
@@ -98,11 +112,11 @@ def check_all_passes_full(g: Geom, x, w, dy, label, passes=("fwd", "bwi", "bww")
     errs = {}
     if "fwd" in passes:
         ref, ref_abs = st_ref.conv_fwd(g, x, w)
-        for dense in variants:
+        for dense in fwd_variants(variants):
             errs["fwd", dense] = assert_close(L.fwd(dense), ref, ref_abs, f"{label} FWD dense={dense}")
     if "bwi" in passes:
         ref, ref_abs = st_ref.conv_bwi(g, dy, w)
-        for dense in variants:
+        for dense in fwd_variants(variants):
             errs["bwi", dense] = assert_close(L.bwi(dense), ref, ref_abs, f"{label} BWI dense={dense}")
     if "bww" in passes:
         ref, ref_abs = st_ref.conv_bww(g, x, dy)
@@ -127,13 +141,13 @@ def check_all_passes_sampled(g: Geom, x, w, dy, label, n_samples=4096, seed=0, v
     L = DeviceLayer(g, x, w, dy)
     cy = sample_coords(g.y_shape, n_samples, seed)
     ref, ref_abs = st_ref.conv_fwd_at(g, x, w, cy)
-    for dense in variants:
+    for dense in fwd_variants(variants):
         got = L.fwd(dense)
         assert np.isfinite(got).all()
         assert_close(got[tuple(cy.T)], ref, ref_abs, f"{label} FWD dense={dense} (sampled)")
     cx = sample_coords(g.x_shape, n_samples, seed + 1)
     ref, ref_abs = st_ref.conv_bwi_at(g, dy, w, cx)
-    for dense in variants:
+    for dense in fwd_variants(variants):
         got = L.bwi(dense)
         assert np.isfinite(got).all()
         assert_close(got[tuple(cx.T)], ref, ref_abs, f"{label} BWI dense={dense} (sampled)")

@@ -46,12 +46,15 @@ def test_validation_happens_on_the_host():
     assert st.st_conv_bww(good, None, None, None, check=False) == 1
     assert st.st_conv_bww_dy(good, None, None, None, check=False) == 1
     assert st.st_conv_bww_auto(good, None, None, None, check=False) == 1
+    assert st.st_conv_fwd_auto(good, None, None, None, check=False) == 1
+    assert st.st_conv_bwi_auto(good, None, None, None, check=False) == 1
     bad = [st.ConvDesc(0, 16, 16, 8, 8, 3, 3), st.ConvDesc(1, 8, 16, 8, 8, 3, 3, 1, 1, 1, 1),
            st.ConvDesc(1, 16, 24, 8, 8, 3, 3, 1, 1, 1, 1), st.ConvDesc(1, 16, 16, 2, 8, 3, 3),
            st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 0, 1), st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 1, 1, -1, 0)]
     for d in bad:
         for fn in (st.st_conv_fwd, st.st_conv_fwd_dense, st.st_conv_bwi, st.st_conv_bwi_dense,
-                   st.st_conv_bww, st.st_conv_bww_dense, st.st_conv_bww_dy, st.st_conv_bww_auto):
+                   st.st_conv_bww, st.st_conv_bww_dense, st.st_conv_bww_dy, st.st_conv_bww_auto,
+                   st.st_conv_fwd_auto, st.st_conv_bwi_auto):
             assert fn(d, 256, 256, 256, check=False) == 2, d
         assert st.st_conv_workspace_bytes(d, st.ST_PASS_BWI) == 0
     with pytest.raises(st.StConvError) as e:
@@ -85,6 +88,13 @@ def test_workspace_query_and_rejection():
         auto = st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW_AUTO)
         assert auto == 256 + max(need, st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW))
         assert st.st_conv_bww_auto(dd, 256, 256, 256, ws=4096, ws_bytes=auto - 1, check=False) == 4
+    # FWD / BWI with the form chosen on the device: counters + both forms' workspaces
+    for pa, pb, fn in ((st.ST_PASS_FWD_AUTO, st.ST_PASS_FWD, st.st_conv_fwd_auto),
+                       (st.ST_PASS_BWI_AUTO, st.ST_PASS_BWI, st.st_conv_bwi_auto)):
+        need = st.st_conv_workspace_bytes(d, pa)
+        assert need == 256 + st.st_conv_workspace_bytes(d, pb, False) + st.st_conv_workspace_bytes(d, pb, True)
+        assert fn(d, 256, 256, 256, ws=None, check=False) == 4
+        assert fn(d, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
     # shapes served by the generic kernel need none
     assert st.st_conv_workspace_bytes(st.ConvDesc(1, 16, 16, 8, 8, 5, 5, 1, 1, 2, 2), st.ST_PASS_BWW_DY) == 0
     assert st.st_conv_workspace_bytes(d, 7) == 0

@@ -219,6 +219,33 @@ def test_bww_auto_selects_the_sparser_operand(g, px, pdy):
     assert np.array_equal(got, L.bww("auto")), "two runs differ"
 
 
+@pytest.mark.parametrize("p,form", [(0.1, True), (0.9, False)])
+def test_fwd_bwi_auto_pick_the_form_by_sparsity(p, form):
+    """st_conv_fwd_auto / st_conv_bwi_auto: with few zeros the result is bit-identical to the dense
+    entry point's, with many to the zero-skipping one's (the two sum in different orders), and the
+    counters hold the zero count of the sampled blocks of the tested operand."""
+    g = Geom(2, 64, 128, 24, 24, 3, 3, 1, 1, 1, 1)      # break-even of this shape: 40 % zeros
+    x, w, dy = synth(g, p, p, seed=61)
+    L = DeviceLayer(g, x, w, dy)
+    assert not np.array_equal(L.fwd(False), L.fwd(True)), "forms indistinguishable: test is void"
+    got = L.fwd("auto")
+    counters = L.auto_ws[:2].cpu().numpy().view(np.uint32)
+    assert tuple(int(c) for c in counters) == sampled_zero_counts(st.pack_activations(x))
+    assert np.array_equal(got, L.fwd(form))
+    got = L.bwi("auto")
+    counters = L.auto_ws[:2].cpu().numpy().view(np.uint32)
+    assert tuple(int(c) for c in counters) == sampled_zero_counts(st.pack_activations(dy))
+    assert np.array_equal(got, L.bwi(form))
+
+
+def test_fwd_auto_1x1_never_takes_the_narrow_sparse_form():
+    g = Geom(2, 64, 64, 12, 12, 1, 1)
+    x, w, dy = synth(g, 0.95, 0.95, seed=62)
+    L = DeviceLayer(g, x, w, dy)
+    assert np.array_equal(L.fwd("auto"), L.fwd(True))
+    assert np.array_equal(L.bwi("auto"), L.bwi(True))
+
+
 def test_config3_resnet3_2_full():
     """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
     L = stgen.RESNET3_2
