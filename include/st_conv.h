@@ -148,7 +148,7 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
  * FWD, dy for BWI; one block of 1024 elements in eight), then both forms are enqueued and the one
  * the count does not select returns at once.  The zero-skipping form runs when the sampled zero
  * fraction reaches the break-even point measured for the geometry (40 % for 3x3 layers with K a
- * multiple of 128, 62 % for narrower ones, 80 % / 60 % for FWD / BWI of stride-2 3x3 layers, 90 %
+ * multiple of 128, 62 % for narrower ones, 80 % / 50 % for FWD / BWI of stride-2 3x3 layers, 90 %
  * for 1x1 layers with K a multiple of 256 and never for other 1x1 layers; always for geometries
  * only the generic kernels cover).  Same tensors and layouts as st_conv_fwd / st_conv_bwi, same
  * result to rounding, no host synchronisation.

@@ -352,7 +352,7 @@ unsigned fwd_sparse_threshold(const Geom &g)
     if (!fwd_sparse_supported(g)) return 0;         // generic kernels: the test only ever removes work
     if (g.R == 1) return g.Ko % 256 == 0 ? 900 : 1001;
     if (g.sw == 2) return 800;
-    if (g.uw == 2) return 600;
+    if (g.uw == 2) return 500;
     return g.Ko % 128 == 0 ? 400 : 620;
 }
 
@@ -369,9 +369,11 @@ hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, flo
     }
     if (g.uw == 2) {
         // BWI of a stride-2 layer: every tested element feeds all 9 taps; tiles have even sides so
-        // that the position of the input samples within a tile is the same for every tile
+        // that the position of the input samples within a tile is the same for every tile.  One
+        // channel per lane and 64-pixel tiles: a dx tile receives only 2.25 taps per pixel and
+        // channel, so the filter registers of a channel must serve as many pixels as possible
+        // (two channels per lane on 4x8 tiles measured 20-45 % slower).
         const bool fourteen = g.Wo % 8 != 0 && g.Wo % 14 == 0;
-        if (wide) return fourteen ? launch_cfg<3, 3, 2, 14, 2, 4, 1, 2, 1>(g, in, f, out, s) : launch_cfg<3, 3, 4, 8, 2, 4, 1, 2, 1>(g, in, f, out, s);
         return fourteen ? launch_cfg<3, 3, 4, 14, 1, 4, 1, 2, 1>(g, in, f, out, s) : launch_cfg<3, 3, 8, 8, 1, 4, 1, 2, 1>(g, in, f, out, s);
     }
     if (g.R == 3 && g.S == 3) {
