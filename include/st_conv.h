@@ -170,6 +170,14 @@ st_status st_conv_bwi_auto(const st_conv_desc *desc, const float *dy, const floa
  */
 size_t st_conv_workspace_bytes(const st_conv_desc *desc, int pass, int dense);
 
+/*
+ * The zero fraction of the tested operand, in per mille, from which st_conv_fwd_auto (pass =
+ * ST_PASS_FWD) or st_conv_bwi_auto (pass = ST_PASS_BWI) runs the zero-skipping form for this
+ * geometry: 0 = always, 1001 = never; -1 for an invalid descriptor or another pass.  Host-side,
+ * no GPU work.
+ */
+int st_conv_sparse_threshold(const st_conv_desc *desc, int pass);
+
 /* Static, NUL-terminated description of a status value. */
 const char *st_status_str(st_status status);
 

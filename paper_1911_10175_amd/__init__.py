@@ -8,7 +8,7 @@ from .binding import (ConvDesc, StConvError, ST_PASS_BWI, ST_PASS_BWI_AUTO, ST_P
                       ST_PASS_BWW_DY, ST_PASS_FWD, ST_PASS_FWD_AUTO, lib_path, load_library, st_conv_bwi,
                       st_conv_bwi_auto, st_conv_bwi_dense, st_conv_bww, st_conv_bww_auto, st_conv_bww_dense,
                       st_conv_bww_dy, st_conv_fwd, st_conv_fwd_auto, st_conv_fwd_dense, st_conv_version,
-                      st_conv_workspace_bytes, st_status_str)
+                      st_conv_sparse_threshold, st_conv_workspace_bytes, st_status_str)
 from .layout import (pack_activations, pack_filters, unpack_activations, unpack_filters)
 
 __all__ = [
@@ -16,6 +16,6 @@ __all__ = [
     "ST_PASS_FWD_AUTO", "ST_PASS_BWI_AUTO", "lib_path", "load_library",
     "st_conv_fwd", "st_conv_fwd_dense", "st_conv_fwd_auto", "st_conv_bwi", "st_conv_bwi_dense", "st_conv_bwi_auto",
     "st_conv_bww", "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_workspace_bytes",
-    "st_status_str", "st_conv_version",
+    "st_conv_sparse_threshold", "st_status_str", "st_conv_version",
     "pack_activations", "unpack_activations", "pack_filters", "unpack_filters",
 ]

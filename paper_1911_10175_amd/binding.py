@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libst_conv.so"
 EXPORTS = ("st_conv_fwd", "st_conv_fwd_dense", "st_conv_bwi", "st_conv_bwi_dense", "st_conv_bww",
            "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_fwd_auto", "st_conv_bwi_auto",
-           "st_conv_workspace_bytes", "st_status_str", "st_conv_version")
+           "st_conv_workspace_bytes", "st_conv_sparse_threshold", "st_status_str", "st_conv_version")
 
 
 class StConvError(RuntimeError):
@@ -88,6 +88,8 @@ def load_library():
             fn.restype = ctypes.c_int
         lib.st_conv_workspace_bytes.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int, ctypes.c_int]
         lib.st_conv_workspace_bytes.restype = ctypes.c_size_t
+        lib.st_conv_sparse_threshold.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int]
+        lib.st_conv_sparse_threshold.restype = ctypes.c_int
         lib.st_status_str.argtypes = [ctypes.c_int]
         lib.st_status_str.restype = ctypes.c_char_p
         lib.st_conv_version.argtypes = []
@@ -124,6 +126,11 @@ def st_status_str(status: int) -> str:
 
 def st_conv_version() -> str:
     return load_library().st_conv_version().decode()
+
+
+def st_conv_sparse_threshold(desc: ConvDesc, conv_pass: int) -> int:
+    c = desc._c()
+    return int(load_library().st_conv_sparse_threshold(ctypes.byref(c), int(conv_pass)))
 
 
 def st_conv_workspace_bytes(desc: ConvDesc, conv_pass: int, dense: bool = False) -> int:

@@ -334,6 +334,20 @@ size_t st_conv_workspace_bytes(const st_conv_desc *desc, int pass, int dense)
     return workspace_bytes(*desc, o, pass, dense != 0);
 }
 
+int st_conv_sparse_threshold(const st_conv_desc *desc, int pass)
+{
+    Dims o;
+    if (validate(desc, &o) != ST_OK) return -1;
+    Geom g = fwd_geom(*desc, o);
+    if (pass == ST_PASS_BWI || pass == ST_PASS_BWI_AUTO) {
+        if (!bwi_as_fwd(*desc, o, &g)) return 0;
+    } else if (pass != ST_PASS_FWD && pass != ST_PASS_FWD_AUTO) {
+        return -1;
+    }
+    if (!st::fwd_sparse_supported(g) || !st::fwd_dense_supported(g)) return 0;
+    return (int)st::fwd_sparse_threshold(g);
+}
+
 const char *st_status_str(st_status status)
 {
     switch (status) {

@@ -174,12 +174,17 @@ __global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restric
     unsigned zeros = 0, seen = 0;
     for (size_t b = blockIdx.x; b < sampled_blocks; b += gridDim.x) {
         const size_t base = b * stride * 1024 + threadIdx.x * 4;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (base + j < n) {
-                zeros += t[base + j] == 0.f ? 1u : 0u;
-                seen += 1u;
-            }
+        if (base + 3 < n) {                              // tensors are 64-byte aligned: one 16-byte load
+            const float4 v = *reinterpret_cast<const float4 *>(t + base);
+            zeros += (v.x == 0.f ? 1u : 0u) + (v.y == 0.f ? 1u : 0u) + (v.z == 0.f ? 1u : 0u) + (v.w == 0.f ? 1u : 0u);
+            seen += 4u;
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (base + j < n) {
+                    zeros += t[base + j] == 0.f ? 1u : 0u;
+                    seen += 1u;
+                }
+        }
     }
     // wavefront sums, workgroup sum, then one pair of atomics per workgroup (a few hundred in all:
     // atomics to one address are serialised by the memory system)
@@ -293,7 +298,7 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
         size_t stride = blocks < 64 ? 1 : 8;
         while ((blocks + stride - 1) / stride > (1u << 20)) stride *= 2;
         const size_t sampled = (blocks + stride - 1) / stride;
-        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 512 ? sampled : 512)), dim3(256), 0, s, t[i],
+        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 1024 ? sampled : 1024)), dim3(256), 0, s, t[i],
                            n[i], (unsigned)stride, sampled, counters + 2 * i);
     }
     return hipGetLastError();

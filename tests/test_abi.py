@@ -105,3 +105,23 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_HERE", str(tmp_path))
     with pytest.raises(FileNotFoundError):
         binding.load_library()
+
+
+def test_sparse_threshold_policy():
+    """Break-even points of the self-selecting FWD / BWI entry points (host-side query)."""
+    F, B = st.ST_PASS_FWD, st.ST_PASS_BWI
+    vgg = st.ConvDesc(16, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_sparse_threshold(vgg, F) == 400 and st.st_conv_sparse_threshold(vgg, B) == 400
+    narrow = st.ConvDesc(16, 64, 64, 56, 56, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_sparse_threshold(narrow, F) == 620
+    # FWD vectorises over K, BWI over C
+    mixed = st.ConvDesc(16, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_sparse_threshold(mixed, F) == 400 and st.st_conv_sparse_threshold(mixed, B) == 620
+    s2 = st.ConvDesc(8, 128, 128, 56, 56, 3, 3, 2, 2, 1, 1)
+    assert st.st_conv_sparse_threshold(s2, F) == 800 and st.st_conv_sparse_threshold(s2, B) == 500
+    pw = st.ConvDesc(8, 64, 256, 56, 56, 1, 1)
+    assert st.st_conv_sparse_threshold(pw, F) == 900 and st.st_conv_sparse_threshold(pw, B) == 1001
+    # only generic kernels: the test can only remove work
+    assert st.st_conv_sparse_threshold(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), F) == 0
+    assert st.st_conv_sparse_threshold(st.ConvDesc(0, 16, 16, 9, 9, 3, 3), F) == -1
+    assert st.st_conv_sparse_threshold(vgg, st.ST_PASS_BWW) == -1
