@@ -168,6 +168,8 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
         __syncthreads();
         if (!wave_active) continue;
 
+        // the mask values of a group are read one group ahead (groups follow each other in memory)
+        float mnext = xT[mpix * 64 + cbl * 16 + mch];
         for (int rp = 0; rp < TH / Cfg::RU; ++rp)
         static_for<0, Cfg::RU>([&](auto PAR) __attribute__((always_inline)) {
         constexpr int par = decltype(PAR)::value;            // row parity (MODE 1), else 0
@@ -175,7 +177,8 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
         for (int b0 = 0; b0 < TW; b0 += GP) {                // groups of GP pixels along the row
             const int g0 = a * TW + b0;
             // non-zero mask of the group: bit 16*j + c for pixel j, channel c of the block
-            const float mval = xT[(g0 + mpix) * 64 + cbl * 16 + mch];
+            const float mval = mnext;
+            if (g0 + GP < TP) mnext = xT[(g0 + GP + mpix) * 64 + cbl * 16 + mch];
             const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
             const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
             if ((mlo | mhi) == 0u) continue;                 // nothing to do for these 4 pixels x 16 channels
@@ -491,8 +494,10 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
         __syncthreads();
         if (!wave_active) continue;
 
+        float mnext = xT[mpix * 64 + cbl * 16 + mch];        // mask values are read one group ahead
         for (int g0 = 0; g0 < P; g0 += GP) {
-            const float mval = xT[(g0 + mpix) * 64 + cbl * 16 + mch];
+            const float mval = mnext;
+            if (g0 + GP < P) mnext = xT[(g0 + GP + mpix) * 64 + cbl * 16 + mch];
             const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
             const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
             if ((mlo | mhi) == 0u) continue;

@@ -343,7 +343,7 @@ bool fwd_sparse_supported(const Geom &g)
     return false;
 }
 
-// Measured break-even points (profiles/config_table.md): the zero-skipping form needs 30-45 % zeros
+// Break-even points measured on the layer shapes of the paper's Table 1: the zero-skipping form needs 30-45 % zeros
 // with 128 output channels per wavefront and about 60 % with 64; the stride-2 FWD tests 2.25 taps
 // per element and its BWI is held by the filter stream of small tiles; a 1x1 layer saves K/64
 // multiply-adds per zero.
