@@ -63,6 +63,11 @@ SMALL = [
     # 1x1
     ("1x1_k128", Geom(2, 64, 128, 12, 12, 1, 1), 0.4, 0.5),
     ("1x1_k64", Geom(2, 256, 64, 9, 11, 1, 1), 0.55, 0.5),
+    # channel counts that are no multiple of the 32-wide MFMA blocks or of the 64 lanes, ragged last pixel chunk
+    ("1x1_k48_c80", Geom(3, 80, 48, 7, 5, 1, 1), 0.5, 0.5),
+    ("1x1_k16_c16", Geom(1, 16, 16, 3, 3, 1, 1), 0.5, 0.5),
+    ("1x1_k208_c96", Geom(2, 96, 208, 14, 14, 1, 1), 0.4, 0.6),
+    ("1x1_k512_c32", Geom(1, 32, 512, 6, 6, 1, 1), 0.5, 0.5),
     ("3x3_stride2", Geom(2, 32, 32, 14, 14, 3, 3, 2, 2, 1, 1), 0.5, 0.5),
     # shapes only the generic kernels cover
     ("5x5_pad2", Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2), 0.5, 0.5),
@@ -163,6 +168,8 @@ STRIDE2 = [
     ("s2 64->64 15x17", Geom(1, 64, 64, 15, 17, 3, 3, 2, 2, 1, 1)),          # odd image sizes
     ("s2 pad0", Geom(2, 32, 32, 17, 17, 3, 3, 2, 2, 0, 0)),                  # FWD tiled, BWI generic
     ("s2 pad2", Geom(1, 16, 128, 12, 20, 3, 3, 2, 2, 2, 2)),
+    ("s2 16->16 tiny", Geom(1, 16, 16, 5, 5, 3, 3, 2, 2, 1, 1)),
+    ("s2 80->48 @9x30", Geom(2, 80, 48, 9, 30, 3, 3, 2, 2, 1, 1)),
     ("s2 256->256 @28", Geom(2, 256, 256, 28, 28, 3, 3, 2, 2, 1, 1)),        # Table 1 resnet4_2/r, channel split 4
 ]
 
