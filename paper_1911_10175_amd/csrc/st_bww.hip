@@ -28,13 +28,6 @@
 namespace st {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
-{
-    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
-}
-
 struct BwwArgs {
     int N, C, K, H, W, OH, OW, pw, ph;
     int tiles_w, tiles_h;      // tiles over the input image (sparse) / the output image (dense)
@@ -87,15 +80,6 @@ struct BwwSparseCfg {
 // zero-skipping kernel: tiles run over the INPUT image; LDS holds the x tile (64 channels) and
 // the dy halo of the tile (64 output channels)
 // ------------------------------------------------------------------------------------------
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
 template <int R, int S, int TH, int TW, int MODE = 0>
 __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
                                                             const float *__restrict__ dy,

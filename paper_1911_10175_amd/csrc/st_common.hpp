@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "st_conv.h"
 
 namespace st {
@@ -36,6 +38,29 @@ struct Geom {
 };
 
 #if defined(__HIPCC__)
+typedef float floatx16 __attribute__((ext_vector_type(16)));       // accumulator block of a 32x32 MFMA
+
+// element offset of pixel (h, w) of channel block cb of image n in the blocked activation layout
+__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
+{
+    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
+}
+
+// f(integral_constant<int, I>) for I = First .. Last-1, fully unrolled with compile-time indices (what
+// keeps register arrays indexed by them in registers)
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// immediate of s_waitcnt that waits until at most n vector-memory loads are outstanding and leaves
+// the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
+
 __device__ __forceinline__ bool form_deselected(const unsigned *sel, int want, unsigned thr)
 {
     if (!sel) return false;

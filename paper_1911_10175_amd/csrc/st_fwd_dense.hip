@@ -22,13 +22,6 @@
 namespace st {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
-{
-    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
-}
-
 // TWD = tile width: 8 (8 rows), 14 (4 rows) or 28 (2 rows); a tile holds at most 64 pixels, i.e.
 // two 32-row MFMA blocks; with 14 or 28 columns the last 8 rows of the second block are padding.
 //
@@ -54,13 +47,21 @@ struct FwdDenseCfg {
     static constexpr int fv(int t) { return MODE == 2 ? (PI ? 2 * (t / NU) : 1) : t / NU; }
     static constexpr int fu(int t) { return MODE == 2 ? (PJ ? 2 * (t % NU) : 1) : t % NU; }
     static constexpr int ftap(int t) { return fv(t) * R + fu(t); }
+    // wavefronts per SIMD the register allocator should aim for: 4, or what the LDS of the
+    // workgroups (two halo buffers per pixel tile, 160 KB per compute unit) leaves room for
+    static constexpr int minw(int kq)
+    {
+        const int fit = 163840 / (2 * (4 / kq) * BUF * 4);
+        return fit >= 4 ? 4 : (fit >= 1 ? fit : 1);
+    }
     static constexpr int XST = 20;                  // floats per staged pixel (16 channels + 4 pad)
     static constexpr int BUF = ((HP * XST + 63) / 64) * 64;   // floats per halo buffer
 };
 
 // KQ = column blocks (of 32 output channels) per workgroup: 1, 2 or 4; TQ = 4/KQ pixel tiles.
 template <int R, int S, int KQ, int TWD, int MODE = 0, int PI = 0, int PJ = 0>
-__global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *__restrict__ in,
+__global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ))) void fwd_dense_kernel(
+    Geom g, const float *__restrict__ in,
                                                            const float *__restrict__ wd,
                                                            float *__restrict__ out, int tiles_w,
                                                            int tiles_h, int kgroups, int total_tiles)
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(256, 4) void fwd_dense_kernel(Geom g, const float *
         }
     };
 
-    constexpr int kWaitOlder = 2 | (0x7 << 4) | (0xF << 8);       // vmcnt(2): all but the 2 newest loads
+    constexpr int kWaitOlder = vmcnt_imm(2);          // all but the 2 newest loads
     float bcur[8], bnxt[8];
     float4 hreg[NLD];
     load_halo(0, hreg);

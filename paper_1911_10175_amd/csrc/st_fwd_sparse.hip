@@ -22,20 +22,6 @@
 namespace st {
 namespace {
 
-__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
-{
-    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
-}
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
 // SD = stride of the correlation (the output samples every SD-th position), SU = spacing of the
 // input samples (SU = 2: the input sits on every second position of the grid the taps slide over,
 // which is how the BWI of a stride-2 layer looks: Sec. 3.3 of the paper, dX receives O*P times
@@ -197,7 +183,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     // order, so this waits for everything older than the NW most recent loads (one filter set).
     constexpr int NW = KPL * S * R;
     static_assert(NW < 64, "vmcnt is a 6-bit counter");
-    constexpr int kWaitOlderSet = (NW & 0xF) | ((NW >> 4) << 14) | (0x7 << 4) | (0xF << 8);
+    constexpr int kWaitOlderSet = vmcnt_imm(NW);
 
     for (int cb = valid ? cb_begin : cb_end; cb < cb_end; ++cb) {
         // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----

@@ -12,11 +12,6 @@
 namespace st {
 namespace {
 
-__device__ __forceinline__ size_t act_off(int n, int cb, int h, int w, int CB, int H, int W)
-{
-    return ((((size_t)n * CB + cb) * H + h) * W + w) * kBlk;
-}
-
 __device__ __forceinline__ size_t flt_off(int kb, int cb, int v, int u, int CB, int S, int R)
 {
     return ((((size_t)kb * CB + cb) * S + v) * R + u) * (kBlk * kBlk);

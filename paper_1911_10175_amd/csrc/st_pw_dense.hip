@@ -24,19 +24,6 @@
 namespace st {
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
-constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
-
 template <int PB, int KB, int DEPTH>
 __global__ __launch_bounds__(256) void pw_dense_kernel(int total_px, int HW, int CiB, int KoB,
                                                        const float *__restrict__ in,
