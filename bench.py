@@ -256,6 +256,14 @@ def main():
     passes["fwd"]["auto_select_ms"] = round(time_pass("fwd_auto", False, args.steps)[0], 4)
     passes["bwi"]["auto_select_ms"] = round(time_pass("bwi_auto", False, args.steps)[0], 4)
 
+    # side measurement: the same zero fraction of x arranged as whole dead (image, channel) planes
+    xdead_h = stgen.dead_channels(stgen.relu_sparse((L.N, L.C, L.H, L.W), 0.0, 200), px, 201)
+    xdead = torch.from_numpy(st.pack_activations(xdead_h)).to(dev)
+    passes["fwd"]["dead_channel_pattern"] = {
+        "zero_fraction": round(stgen.zero_fraction(xdead_h), 4),
+        "sparse_ms": round(time_pass("fwd", False, args.steps, xdead)[0], 4)}
+    del xdead, xdead_h
+
     # ---- roofline of the dominant kernel ----
     # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy), so the
     # event time of st_conv_fwd is that kernel's launch duration.  Algorithmic work per launch:

@@ -185,6 +185,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     static_assert(NW < 64, "vmcnt is a 6-bit counter");
     constexpr int kWaitOlderSet = vmcnt_imm(NW);
 
+    unsigned alive = 0u;
     for (int cb = valid ? cb_begin : cb_end; cb < cb_end; ++cb) {
         // ---- stage the halo of this 16-channel block in LDS, transposed to [channel][pixel] ----
         __builtin_amdgcn_wave_barrier();
@@ -195,6 +196,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
             int sl = lane;
             asm volatile("" : "+v"(sl));
             const float *plane = in + act_off(n, cb, 0, 0, CiB, g.Hi, g.Wi);      // wave-uniform base
+            unsigned nz0 = 0u, nz1 = 0u, nz2 = 0u, nz3 = 0u;    // OR of the value bits per staged component of this lane
 #pragma unroll
             for (int jj = 0; jj < NST; ++jj) {
                 const int idx = jj * kWave + sl;
@@ -208,21 +210,52 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
                     lds[(q * 4 + 1) * PST + pix] = val.y;
                     lds[(q * 4 + 2) * PST + pix] = val.z;
                     lds[(q * 4 + 3) * PST + pix] = val.w;
+                    nz0 |= __builtin_bit_cast(unsigned, val.x);
+                    nz1 |= __builtin_bit_cast(unsigned, val.y);
+                    nz2 |= __builtin_bit_cast(unsigned, val.z);
+                    nz3 |= __builtin_bit_cast(unsigned, val.w);
                 }
+            }
+            // Channels of this block with at least one non-zero in the halo (ReLU leaves whole
+            // channels of an image dead): a lane's slots all belong to channel quarter lane % 4
+            // (64 % 4 == 0), so channel 4*q + comp is alive iff some lane = q (mod 4) saw a
+            // non-zero in component comp.  -0 counts as zero, denormals do not.
+            alive = 0u;
+            const unsigned nzv[4] = {nz0, nz1, nz2, nz3};
+#pragma unroll
+            for (int comp = 0; comp < 4; ++comp) {
+                const unsigned long long m = __builtin_amdgcn_ballot_w64((nzv[comp] & 0x7fffffffu) != 0u);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (m & (0x1111111111111111ull << q)) alive |= 1u << (q * 4 + comp);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        for (int ci = 0; ci < kBlk; ci += 2) {
-            const int c = cb * kBlk + ci;
-            load_w(c + 1, wB);
+        // Dead channels cost neither a filter load nor a pass over the masks.  wA holds the filters
+        // of channel 0 of this block on entry and of the next block on exit; the filters of the next
+        // alive channel are always in flight while the current one is processed.
+        const int cnext = min((cb + 1) * kBlk, c_last);      // first channel of the next block
+        unsigned bits = __builtin_amdgcn_readfirstlane(alive);      // wave-uniform by construction; say so
+        int c0 = bits ? __builtin_ctz(bits) : kBlk;         // kBlk = none (left)
+        bits &= bits - 1u;                                  // no-op on 0
+        if (c0 != 0) load_w(c0 < kBlk ? cb * kBlk + c0 : cnext, wA);
+        while (c0 < kBlk) {
+            // the next two alive channels; when none is left the filters of the next block's channel 0
+            // are fetched instead, which also keeps the number of loads per step fixed
+            const int c1 = bits ? __builtin_ctz(bits) : kBlk;
+            bits &= bits - 1u;
+            const int c2 = bits ? __builtin_ctz(bits) : kBlk;
+            bits &= bits - 1u;
+            load_w(c1 < kBlk ? cb * kBlk + c1 : cnext, wB);
             __builtin_amdgcn_s_waitcnt(kWaitOlderSet);     // wA has arrived; wB stays in flight
-            process(ci, wA);
-            load_w(min(c + 2, c_last), wA);
+            process(c0, wA);
+            load_w(c2 < kBlk ? cb * kBlk + c2 : cnext, wA);
             __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
-            process(ci + 1, wB);
+            if (c1 < kBlk) process(c1, wB);
+            c0 = c2;
         }
     }
 

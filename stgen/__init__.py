@@ -97,6 +97,14 @@ def bernoulli_masked(shape, q: float, stream_g: int, stream_m: int) -> np.ndarra
     return (g * m).reshape(shape)
 
 
+def dead_channels(a: np.ndarray, p_dead: float, stream: int) -> np.ndarray:
+    """Copy of an [N][C][H][W] tensor with whole (image, channel) planes set to zero, each with
+    probability p_dead: the clustered form ReLU zeros take when a filter does not fire on an image."""
+    n, c = a.shape[:2]
+    keep = (uniform(stream, n * c) >= p_dead).astype(a.dtype).reshape(n, c, 1, 1)
+    return a * keep
+
+
 def he_normal(shape_kcsr, stream: int) -> np.ndarray:
     """fp32 filters ~ N(0, 2/(C*S*R)) in plain [K][C][S][R] order."""
     k, c, s, r = shape_kcsr

@@ -253,6 +253,31 @@ def test_fwd_auto_1x1_never_takes_the_narrow_sparse_form():
     assert np.array_equal(L.bwi("auto"), L.bwi(True))
 
 
+def test_dead_channels_are_skipped_correctly():
+    """Whole channels of an image that are zero (no filter load, no mask pass in FWD/BWI): every
+    count of alive channels per 16-channel block, a dead first channel, dead blocks, dead images."""
+    g = Geom(3, 80, 128, 12, 16, 3, 3, 1, 1, 1, 1)
+    x, w, dy = synth(g, 0.3, 0.3, seed=71)
+    # image 0: block b keeps its first b*3 + 1 channels' complement pattern; image 1: random; image 2: all dead
+    for b in range(5):
+        alive = {0: [], 1: [0], 2: [15], 3: [1, 2, 3], 4: list(range(1, 16))}[b]
+        for ci in range(16):
+            if ci not in alive:
+                x[0, b * 16 + ci] = 0.0
+    x[1:2] = stgen.dead_channels(x[1:2], 0.5, 72)
+    x[2] = 0.0
+    dy[0, 5:] = 0.0                                        # BWI: K = 128, most channels of image 0 dead
+    dy[1:2] = stgen.dead_channels(dy[1:2], 0.6, 73)
+    dy[2, ::2] = -0.0                                      # -0 planes count as dead
+    check_all_passes_full(g, x, w, dy, "dead-channels")
+    # 1x1 and stride 2 run the same channel loop
+    for g2 in (Geom(2, 64, 256, 9, 9, 1, 1), Geom(2, 48, 128, 14, 14, 3, 3, 2, 2, 1, 1)):
+        x, w, dy = synth(g2, 0.3, 0.3, seed=74)
+        x = stgen.dead_channels(x, 0.6, 75)
+        dy = stgen.dead_channels(dy, 0.6, 76)
+        check_all_passes_full(g2, x, w, dy, "dead-channels-2")
+
+
 def test_config3_resnet3_2_full():
     """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
     L = stgen.RESNET3_2

@@ -77,3 +77,14 @@ def test_workload_table():
     assert len(stack) == 12 and sum(l.flops for l in stack) == 976_635_297_792
     x, w, dy = stgen.make_layer_tensors(stgen.TINY, seed=0)
     assert x.shape == (1, 16, 8, 8) and w.shape == (16, 16, 3, 3) and dy is None
+
+
+def test_dead_channels_zero_whole_planes():
+    a = stgen.relu_sparse((4, 32, 5, 6), 0.0, 7)
+    b = stgen.dead_channels(a, 0.5, 8)
+    planes = np.abs(b).reshape(4 * 32, -1).sum(axis=1)
+    dead = int((planes == 0).sum())
+    assert 40 < dead < 90                                  # about half of the 128 planes
+    alive = planes != 0
+    assert np.array_equal(b.reshape(128, -1)[alive], a.reshape(128, -1)[alive])
+    assert np.array_equal(stgen.dead_channels(a, 0.5, 8), b)      # deterministic
