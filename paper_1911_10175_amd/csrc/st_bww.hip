@@ -237,7 +237,8 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
     __shared__ __attribute__((aligned(16))) float dyT[TP * 64];
     __shared__ __attribute__((aligned(16))) float xT[HP * 64];
 
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int l32 = lane % 32, half = lane / 32;
     const int kh = wave % 2, ch = wave / 2;
     const int split = blockIdx.x;
@@ -330,7 +331,8 @@ __global__ __launch_bounds__(256) void pw_bww_dense_kernel(BwwArgs A, const floa
     __shared__ __attribute__((aligned(16))) float xs[P * CW];
     __shared__ __attribute__((aligned(16))) float ds[P * CW];
 
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int l32 = lane % 32, half = lane / 32;
     const int wk = wave % 2, wc = wave / 2;
     const int split = blockIdx.x;

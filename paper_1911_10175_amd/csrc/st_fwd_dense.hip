@@ -73,7 +73,8 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
     constexpr int NLD = (HP * 4 + KQ * 64 - 1) / (KQ * 64);      // float4 loads per lane and block
     __shared__ __attribute__((aligned(16))) float lds_all[2][TQ][BUF];
 
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int kqi = wave % KQ, tqi = wave / KQ;
     const int kg = blockIdx.x % kgroups, tg = blockIdx.x / kgroups;
     const int tile = tg * TQ + tqi;

@@ -56,7 +56,8 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
     __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][kBlk * PST];
 
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int cpart = wave % CS;                    // which share of the input channels
     // Workgroup -> (tile slot, output-channel tile).  Consecutive workgroup ids are dealt round-robin
     // to the 8 XCDs, each with its own L2; workgroups 8 ids apart run on the same XCD one after the

@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256) void pw_dense_kernel(int total_px, int HW, int
                                                        const unsigned *sel, unsigned thr)
 {
     if (form_deselected(sel, 1, thr)) return;
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int l32 = lane % 32, half = lane / 32;
     // workgroup id -> (pixel group, channel group): the channel groups of one pixel group get ids that
     // are equal modulo 8, i.e. run on the same XCD, and share the input through that XCD's L2
