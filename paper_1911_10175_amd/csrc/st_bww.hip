@@ -700,6 +700,9 @@ BwwArgs make_args_s2_dy(const st_conv_desc &d)
 
 bool bww_fast_supported(const st_conv_desc &d)
 {
+    // gridDim.y carries (output-channel group, input-channel group), at least 32 channels each, with
+    // either operand in either role
+    if ((long long)ceil_div(d.K, 32) * ceil_div(d.C, 32) > 65535) return false;
     if (bww_s2(d)) return (long long)d.N * ceil_div(d.H, 4) * ceil_div(d.W, 8) <= 0x7fffffffLL;
     if (d.stride_w != 1 || d.stride_h != 1) return false;
     const long long units = (long long)d.N * ceil_div(d.H + 2 * d.pad_h, 8) * ceil_div(d.W + 2 * d.pad_w, 16);
