@@ -111,6 +111,11 @@ bool fwd_dense_supported(const Geom &g);
 size_t fwd_dense_filter_bytes(const Geom &g);
 hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w, float *wd, hipStream_t s);
 hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s);
+// 1x1 layers with small filter matrices: whole filter in LDS, read from the library layout (no copy
+// in the workspace needed); transpose selects the BWI form
+bool pw_dense_direct_supported(const Geom &g);
+hipError_t launch_pw_dense_direct(const Geom &g, bool transpose, const float *in, const float *w, float *out,
+                                  hipStream_t s);
 // 1x1 layers: matrix product per pixel, no LDS (called by launch_fwd_dense)
 hipError_t launch_pw_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s);
 

@@ -122,6 +122,7 @@ st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *
     if (dense) {
         if (!st::fwd_dense_supported(g)) return dev(st::launch_generic_fwd(*d, x, w, y, false, s));
         if (!ws_ok(ws, ws_bytes, st::fwd_dense_filter_bytes(g))) return ST_ERR_WORKSPACE;
+        if (st::pw_dense_direct_supported(g)) return dev(st::launch_pw_dense_direct(g, false, x, w, y, s));
         float *wd = static_cast<float *>(ws);
         if (st::launch_reformat_filters(g, false, w, wd, s) != hipSuccess) return ST_ERR_DEVICE;
         return dev(st::launch_fwd_dense(g, x, wd, y, s));
@@ -145,6 +146,7 @@ st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float 
     float *wt = static_cast<float *>(ws);
     if (dense) {
         if (!ws_ok(ws, ws_bytes, st::fwd_dense_filter_bytes(g))) return ST_ERR_WORKSPACE;
+        if (st::pw_dense_direct_supported(g)) return dev(st::launch_pw_dense_direct(g, true, dy, w, dx, s));
         if (st::launch_reformat_filters(g, true, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
         return dev(st::launch_fwd_dense(g, dy, wt, dx, s));
     }
@@ -229,7 +231,9 @@ st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float 
     if (e != hipSuccess) return ST_ERR_DEVICE;
     // dense form
     g.want = 1;
-    if (fast_dense) {
+    if (fast_dense && st::pw_dense_direct_supported(g)) {
+        e = st::launch_pw_dense_direct(g, bwi, act, w, out, s);
+    } else if (fast_dense) {
         if (st::launch_reformat_filters(g, bwi, w, ws_dense, s) != hipSuccess) return ST_ERR_DEVICE;
         e = st::launch_fwd_dense(g, act, ws_dense, out, s);
     } else {

@@ -211,10 +211,12 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
                     lds[(q * 4 + 1) * PST + pix] = val.y;
                     lds[(q * 4 + 2) * PST + pix] = val.z;
                     lds[(q * 4 + 3) * PST + pix] = val.w;
-                    nz0 |= __builtin_bit_cast(unsigned, val.x);
-                    nz1 |= __builtin_bit_cast(unsigned, val.y);
-                    nz2 |= __builtin_bit_cast(unsigned, val.z);
-                    nz3 |= __builtin_bit_cast(unsigned, val.w);
+                    if constexpr (R * S != 1) {
+                        nz0 |= __builtin_bit_cast(unsigned, val.x);
+                        nz1 |= __builtin_bit_cast(unsigned, val.y);
+                        nz2 |= __builtin_bit_cast(unsigned, val.z);
+                        nz3 |= __builtin_bit_cast(unsigned, val.w);
+                    }
                 }
             }
             // Channels of this block with at least one non-zero in the halo (ReLU leaves whole
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
             alive = 0u;
             const unsigned nzv[4] = {nz0, nz1, nz2, nz3};
 #pragma unroll
-            for (int comp = 0; comp < 4; ++comp) {
+            for (int comp = 0; comp < (R * S != 1 ? 4 : 0); ++comp) {
                 const unsigned long long m = __builtin_amdgcn_ballot_w64((nzv[comp] & 0x7fffffffu) != 0u);
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
@@ -235,6 +237,20 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
+        if constexpr (R * S == 1) {
+            // 1x1: a channel step is only TH*TW tests long, so the walk over the alive mask would cost
+            // more than it saves; every channel is processed
+            for (int ci = 0; ci < kBlk; ci += 2) {
+                const int c = cb * kBlk + ci;
+                load_w(c + 1, wB);
+                __builtin_amdgcn_s_waitcnt(kWaitOlderSet);     // wA has arrived; wB stays in flight
+                process(ci, wA);
+                load_w(min(c + 2, c_last), wA);
+                __builtin_amdgcn_s_waitcnt(kWaitOlderSet);
+                process(ci + 1, wB);
+            }
+            continue;
+        }
         // Dead channels cost neither a filter load nor a pass over the masks.  wA holds the filters
         // of channel 0 of this block on entry and of the next block on exit; the filters of the next
         // alive channel are always in flight while the current one is processed.

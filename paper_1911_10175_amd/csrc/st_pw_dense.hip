@@ -157,7 +157,160 @@ hipError_t launch_pw(const Geom &g, const float *in, const float *wd, float *out
     return hipGetLastError();
 }
 
+// Variant for layers whose filters fit in LDS (at most 16 K elements, e.g. 256 -> 64, 64 -> 256,
+// 64 -> 64: the bandwidth-bound 1x1 layers of the 56x56 ResNet stage).  A workgroup copies the whole
+// filter matrix into LDS once and then walks pixel tiles of 32 pixels per wavefront; a wavefront
+// computes all K output channels of its tile, so an input element is fetched from memory exactly
+// once and the only vector-memory traffic in the loop is the input itself; the filter operand is
+// read from LDS with 16-byte reads that touch consecutive addresses in consecutive lanes.
+template <int KB, int DEPTH>
+__global__ __launch_bounds__(256, 2) void pw_dense_lds_kernel(int total_px, int HW, int CiB, int KoB,
+                                                              const float *__restrict__ in,
+                                                              const float *__restrict__ w, int transpose,
+                                                              float *__restrict__ out, const unsigned *sel,
+                                                              unsigned thr)
+{
+    if (form_deselected(sel, 1, thr)) return;
+    extern __shared__ __attribute__((aligned(16))) float wl[];      // [cb][kb][q][lane][4 c]
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
+    const int l32 = lane % 32, half = lane / 32;
+
+    // Filter copy straight from the library layout [K/16][C/16][16 c][16 k] (no reformatting pass):
+    // LDS float4 (cb, kb, q, lane = (half, k % 32)) holds channels c = 16*cb + 8*half + 4*q + 0..3 of
+    // output channel k = 32*kb + lane % 32; transpose = the BWI form, where the roles of the two
+    // channel dimensions are exchanged.  Output channels beyond Ko are zero.
+    {
+        float4 *dst = reinterpret_cast<float4 *>(wl);
+        const int total4 = KB * CiB * 128;
+        const int Ko = KoB * kBlk;
+        for (int i = threadIdx.x; i < total4; i += 256) {
+            const int sl32 = i & 31, shalf = (i >> 5) & 1, q = (i >> 6) & 1;
+            const int blk = i >> 7, kb = blk % KB, cb = blk / KB;
+            const int k = kb * 32 + sl32, c0 = cb * kBlk + shalf * 8 + q * 4;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (k < Ko) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int c = c0 + e;
+                    v[e] = transpose ? w[((size_t)(c / kBlk) * KoB + k / kBlk) * (kBlk * kBlk) + (k % kBlk) * kBlk + c % kBlk]
+                                     : w[((size_t)(k / kBlk) * CiB + c / kBlk) * (kBlk * kBlk) + (c % kBlk) * kBlk + k % kBlk];
+                }
+            }
+            dst[i] = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    }
+    __syncthreads();
+    const float4 *wl4 = reinterpret_cast<const float4 *>(wl) + lane;
+
+    const size_t plane = (size_t)HW * kBlk;
+    const int ntiles = (total_px + 31) / 32;
+    const int Ko = KoB * kBlk;
+    constexpr int kWaitOlder = vmcnt_imm((DEPTH - 1) * 2);
+
+    for (int tile = blockIdx.x * 4 + wave; tile < ntiles; tile += gridDim.x * 4) {
+        int gp = tile * 32 + l32;
+        const bool pvalid = gp < total_px;
+        if (!pvalid) gp = total_px - 1;
+        const int n = gp / HW, p = gp % HW;
+        const float *xin = in + ((size_t)n * CiB * HW + p) * kBlk + half * 8;
+        float *yout = out + ((size_t)n * KoB * HW + p) * kBlk;
+
+        floatx16 acc[KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[kb][r] = 0.f;
+
+        float4 xr[DEPTH][2];
+        static_for<0, DEPTH - 1>([&](auto J) __attribute__((always_inline)) {
+            constexpr int j = decltype(J)::value;
+            const float4 *px = reinterpret_cast<const float4 *>(xin + (size_t)min(j, CiB - 1) * plane);
+            xr[j][0] = px[0];
+            xr[j][1] = px[1];
+        });
+        // CiB is a multiple of DEPTH (checked by the host): whole rotations of the register slots
+        for (int cb0 = 0; cb0 < CiB; cb0 += DEPTH)
+            static_for<0, DEPTH>([&](auto J) __attribute__((always_inline)) {
+                constexpr int j = decltype(J)::value;
+                const int cb = cb0 + j;
+                const float4 *px = reinterpret_cast<const float4 *>(xin + (size_t)min(cb + DEPTH - 1, CiB - 1) * plane);
+                xr[(j + DEPTH - 1) % DEPTH][0] = px[0];
+                xr[(j + DEPTH - 1) % DEPTH][1] = px[1];
+                float4 wv[KB][2];
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    wv[kb][0] = wl4[((cb * KB + kb) * 2 + 0) * 64];
+                    wv[kb][1] = wl4[((cb * KB + kb) * 2 + 1) * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(kWaitOlder);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb) {
+                        const float a = q < 4 ? wv[kb][0][q] : wv[kb][1][q - 4];
+                        const float b = q < 4 ? xr[j][0][q] : xr[j][1][q - 4];
+                        acc[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[kb], 0, 0, 0);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int k = kb * 32 + 8 * gq + 4 * half;
+                if (pvalid && k < Ko) {
+                    const float4 v = make_float4(acc[kb][4 * gq], acc[kb][4 * gq + 1], acc[kb][4 * gq + 2],
+                                                 acc[kb][4 * gq + 3]);
+                    *reinterpret_cast<float4 *>(yout + (size_t)(k / kBlk) * plane + k % kBlk) = v;
+                }
+            }
+    }
+}
+
+template <int KB>
+hipError_t launch_pw_lds(const Geom &g, bool transpose, const float *in, const float *w, float *out, hipStream_t s)
+{
+    const int HW = g.Ho * g.Wo;
+    const long long total_px = (long long)g.N * HW;
+    const int CiB = g.Ci / kBlk;
+    const size_t lds = (size_t)KB * 32 * g.Ci * sizeof(float);
+    const long long ntiles = (total_px + 31) / 32;
+    // two workgroups per compute unit (LDS permitting); fewer when there are not enough tiles
+    long long blocks = 512;
+    if (blocks * 4 > ntiles) blocks = (ntiles + 3) / 4;
+    auto kern = pw_dense_lds_kernel<KB, 4>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, (int)total_px, HW, CiB, g.Ko / kBlk, in, w,
+                       transpose ? 1 : 0, out, g.sel, g.thr);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// 1x1 layers whose filters fit in LDS (64 KB with the output channels padded to 64, 128 or 256) and
+// that have enough pixels to occupy the chip: computed straight from the library filter layout.
+bool pw_dense_direct_supported(const Geom &g)
+{
+    if (g.R != 1 || g.S != 1 || g.sw != 1 || g.sh != 1 || g.uw != 1 || g.uh != 1 || g.pw != 0 || g.ph != 0) return false;
+    const int kb_all = g.Ko <= 64 ? 2 : (g.Ko <= 128 ? 4 : 8);
+    const long long total_px = (long long)g.N * g.Ho * g.Wo;
+    return g.Ko <= 256 && (size_t)kb_all * 32 * g.Ci * sizeof(float) <= 64 * 1024 && (g.Ci / kBlk) % 4 == 0 &&
+           total_px >= 8192 && total_px <= 0x7fffff00LL;
+}
+
+hipError_t launch_pw_dense_direct(const Geom &g, bool transpose, const float *in, const float *w, float *out,
+                                  hipStream_t s)
+{
+    if (g.Ko <= 64) return launch_pw_lds<2>(g, transpose, in, w, out, s);
+    if (g.Ko <= 128) return launch_pw_lds<4>(g, transpose, in, w, out, s);
+    return launch_pw_lds<8>(g, transpose, in, w, out, s);
+}
 
 // Requires fwd_dense_supported(g) with R = S = 1 (unit stride, no padding: Ho = Hi, Wo = Wi) and the
 // filter copy of launch_reformat_filters, whose output channels are padded to a multiple of 128.
