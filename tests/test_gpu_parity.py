@@ -278,6 +278,40 @@ def test_dead_channels_are_skipped_correctly():
         check_all_passes_full(g2, x, w, dy, "dead-channels-2")
 
 
+def random_geometries(count, seed):
+    """Seeded mix of small geometries over everything the descriptor allows: filter sizes 1/3/5
+    (square and not), strides 1/2, paddings 0..2, odd image sizes, channel counts 16..160."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R, S = (int(v) for v in rng.choice([1, 3, 3, 3, 5], 2))
+        if rng.random() < 0.7:
+            S = R
+        sw = sh = int(rng.choice([1, 1, 2]))
+        pw, ph = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        if rng.random() < 0.6:
+            pw, ph = (R - 1) // 2, (S - 1) // 2
+        H, W = int(rng.integers(3, 21)), int(rng.integers(3, 21))
+        if H + 2 * ph < S or W + 2 * pw < R:
+            continue
+        C, K = 16 * int(rng.integers(1, 11)), 16 * int(rng.integers(1, 11))
+        out.append(Geom(int(rng.integers(1, 4)), C, K, H, W, R, S, sw, sh, pw, ph))
+    return out
+
+
+RANDOM_GEOMS = random_geometries(48, seed=2024)
+
+
+@pytest.mark.parametrize("i", range(len(RANDOM_GEOMS)))
+def test_random_geometries_all_entry_points(i):
+    g = RANDOM_GEOMS[i]
+    px, pdy = [(0.5, 0.5), (0.2, 0.8), (0.9, 0.3)][i % 3]
+    x, w, dy = synth(g, px, pdy, seed=100 + i)
+    if i % 4 == 0:
+        x = stgen.dead_channels(x, 0.4, 900 + i)
+    check_all_passes_full(g, x, w, dy, f"random#{i} {g}")
+
+
 def test_config3_resnet3_2_full():
     """N=32, C=K=128, 28x28, 3x3: x 50 % zeros, dy 45 % zeros; every element checked."""
     L = stgen.RESNET3_2
