@@ -272,7 +272,7 @@ def main():
     fwd_avg_ms = passes["fwd"]["sparse_avg_ms"]
     achieved = F * (1 - px) / (fwd_avg_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4,4> (st_conv_fwd; st_conv_bwi runs the same kernel on dy)",
+        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4,4,1,1,0> (st_conv_fwd; st_conv_bwi runs the same kernel on dy)",
         "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_FP32_VECTOR, 4),
         "peak_unpacked_fma": PEAK_FP32_FMA, "frac_of_unpacked_fma_peak": round(achieved / PEAK_FP32_FMA, 4),

@@ -99,12 +99,14 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
 // dense one for this geometry (measured; 1001 = never)
 unsigned fwd_sparse_threshold(const Geom &g);
 
-// filter transposition for stride-1 BWI: wt[C/16][K/16][S][R][16 k][16 c] with taps reversed
-hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s);
-
 // unit-stride fast paths
 bool fwd_sparse_supported(const Geom &g);
-hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s);
+// the zero-skipping kernel reads filters from a copy in wavefront order (fwd_sparse_filter_bytes)
+// written by launch_wave_filters from the layer's filters w; transpose selects the BWI form (channel
+// roles swapped, taps reversed); g is the geometry of the correlation the kernel runs
+size_t fwd_sparse_filter_bytes(const Geom &g);
+hipError_t launch_wave_filters(const Geom &g, bool transpose, const float *w, float *wl, hipStream_t s);
+hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *wl, float *out, hipStream_t s);
 bool fwd_dense_supported(const Geom &g);
 // the dense kernel reads filters from a reformatted copy (fwd_dense_filter_bytes) written by
 // launch_reformat_filters; transpose selects the BWI form (channel roles swapped, taps reversed)

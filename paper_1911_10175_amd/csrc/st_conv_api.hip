@@ -56,11 +56,6 @@ bool bwi_as_fwd(const st_conv_desc &d, const Dims &o, Geom *g)
     return true;
 }
 
-size_t filter_bytes(const st_conv_desc &d)
-{
-    return (size_t)d.K * d.C * d.S * d.R * sizeof(float);
-}
-
 bool ws_ok(const void *ws, size_t have, size_t need)
 {
     if (need == 0) return true;
@@ -78,13 +73,14 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
     switch (pass) {
     case ST_PASS_FWD: {
         const Geom g = fwd_geom(d, o);
-        return dense && st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
+        if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
+        return st::fwd_sparse_supported(g) ? st::fwd_sparse_filter_bytes(g) : 0;
     }
     case ST_PASS_BWI: {
         Geom g;
         if (!bwi_as_fwd(d, o, &g)) return 0;
         if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
-        return st::fwd_sparse_supported(g) ? filter_bytes(d) : 0;
+        return st::fwd_sparse_supported(g) ? st::fwd_sparse_filter_bytes(g) : 0;
     }
     case ST_PASS_BWW:
         if (!st::bww_fast_supported(d)) return 0;
@@ -127,8 +123,11 @@ st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *
         if (st::launch_reformat_filters(g, false, w, wd, s) != hipSuccess) return ST_ERR_DEVICE;
         return dev(st::launch_fwd_dense(g, x, wd, y, s));
     }
-    if (st::fwd_sparse_supported(g)) return dev(st::launch_fwd_sparse(g, x, w, y, s));
-    return dev(st::launch_generic_fwd(*d, x, w, y, true, s));
+    if (!st::fwd_sparse_supported(g)) return dev(st::launch_generic_fwd(*d, x, w, y, true, s));
+    if (!ws_ok(ws, ws_bytes, st::fwd_sparse_filter_bytes(g))) return ST_ERR_WORKSPACE;
+    float *wl = static_cast<float *>(ws);
+    if (st::launch_wave_filters(g, false, w, wl, s) != hipSuccess) return ST_ERR_DEVICE;
+    return dev(st::launch_fwd_sparse(g, x, wl, y, s));
 }
 
 st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,
@@ -150,8 +149,8 @@ st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float 
         if (st::launch_reformat_filters(g, true, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
         return dev(st::launch_fwd_dense(g, dy, wt, dx, s));
     }
-    if (!ws_ok(ws, ws_bytes, filter_bytes(*d))) return ST_ERR_WORKSPACE;
-    if (st::launch_transpose_filters(*d, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
+    if (!ws_ok(ws, ws_bytes, st::fwd_sparse_filter_bytes(g))) return ST_ERR_WORKSPACE;
+    if (st::launch_wave_filters(g, true, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
     return dev(st::launch_fwd_sparse(g, dy, wt, dx, s));
 }
 
@@ -218,12 +217,8 @@ st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float 
     // zero-skipping form
     g.want = 0;
     if (fast_sparse) {
-        const float *f = w;
-        if (bwi) {
-            if (st::launch_transpose_filters(*d, w, ws_sparse, s) != hipSuccess) return ST_ERR_DEVICE;
-            f = ws_sparse;
-        }
-        e = st::launch_fwd_sparse(g, act, f, out, s);
+        if (st::launch_wave_filters(g, bwi, w, ws_sparse, s) != hipSuccess) return ST_ERR_DEVICE;
+        e = st::launch_fwd_sparse(g, act, ws_sparse, out, s);
     } else {
         e = bwi ? st::launch_generic_bwi(*d, act, w, out, true, s, sel, g.thr)
                 : st::launch_generic_fwd(*d, act, w, out, true, s, sel, g.thr);

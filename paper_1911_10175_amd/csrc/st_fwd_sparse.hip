@@ -13,7 +13,9 @@
 //    to R*S*KPL multiply-adds of that element (T of Sec. 3.1).  A clear bit is a scalar branch
 //    over all of them, taken by the whole wavefront, so no lane ever idles on a zero.
 //  * Filters for the current input channel (R*S*KPL values per lane) sit in registers and are
-//    reused by every non-zero pixel of the tile; they stream from L2, 64 B per 16 lanes.
+//    reused by every non-zero pixel of the tile; they stream from L2 out of a copy of the filters
+//    in wavefront order ([Ko/64][Ci][S][R][64 k], written before every launch), 256 contiguous
+//    bytes per load instruction.
 #include <cstdlib>
 #include <type_traits>
 
@@ -87,24 +89,24 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
 #pragma unroll
         for (int i = 0; i < TH * TW; ++i) acc[j][i] = 0.f;
 
-    // filter pointer of this lane's channel(s): element [kb][cb][v][u][ci][ki]
+    // filter pointer of this lane's channel(s) in the wavefront-ordered copy: element [k/64][c][v][u][k%64]
     const float *fp[KPL];
     bool kact[KPL];
 #pragma unroll
     for (int j = 0; j < KPL; ++j) {
         const int k = kt * Cfg::KT + j * kWave + lane;
         kact[j] = k < g.Ko;
-        const int kb = kact[j] ? k / kBlk : 0;
-        fp[j] = f + (size_t)kb * CiB * (S * R * kBlk * kBlk) + (k % kBlk);
+        // group of 64 channels this lane belongs to; an inactive lane reads element 0 (always written)
+        fp[j] = f + (kact[j] ? (size_t)(k / kWave) * g.Ci * (S * R * kWave) + lane : 0);
     }
 
     // filters of one input channel (flat index c = 16*cb + ci): R*S*KPL registers per lane
     auto load_w = [&](int c, float (&wv)[KPL][S * R]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < KPL; ++j) {
-            const float *p = fp[j] + (size_t)(c / kBlk) * (S * R * kBlk * kBlk) + (c % kBlk) * kBlk;
+            const float *p = fp[j] + (size_t)c * (S * R * kWave);
 #pragma unroll
-            for (int tp = 0; tp < S * R; ++tp) wv[j][tp] = p[tp * (kBlk * kBlk)];
+            for (int tp = 0; tp < S * R; ++tp) wv[j][tp] = p[tp * kWave];
         }
     };
 
@@ -390,6 +392,58 @@ unsigned fwd_sparse_threshold(const Geom &g)
     if (g.sw == 2) return 800;
     if (g.uw == 2) return 500;
     return g.Ko % 128 == 0 ? 400 : 620;
+}
+
+namespace {
+
+// Filters in the order the wavefronts read them: wl[Ko/64][Ci][S][R][64 k] for the correlation g the
+// kernel runs (Ko rounded up to whole groups of 64; the padding is never written and never used).
+// One load instruction of a wavefront then covers 256 contiguous bytes instead of four 64-byte pieces of
+// four cache lines, and the nine taps of a channel sit at immediate offsets of one address.  transpose
+// selects the BWI form (channel roles exchanged, taps reversed; SparseTrain Sec. 3.3): KB x CB are
+// the filter blocks of the LAYER, w its filters in the library layout.
+template <bool TRANSPOSE>
+__global__ __launch_bounds__(256) void wave_filters_kernel(int KB, int CB, int S, int R,
+                                                           const float *__restrict__ w, float *__restrict__ wl)
+{
+    __shared__ float tile[kBlk][kBlk + 1];
+    int t = blockIdx.x;
+    const int u = t % R; t /= R;
+    const int v = t % S; t /= S;
+    const int cb = t % CB;
+    const int kb = t / CB;
+    const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
+    const size_t src = ((((size_t)kb * CB + cb) * S + v) * R + u) * (kBlk * kBlk);        // [ci = a][ki = b]
+    const int SR = S * R;
+    if constexpr (!TRANSPOSE) {
+        const int k = kb * kBlk + b, c = cb * kBlk + a;
+        wl[((size_t)(k / kWave) * (CB * kBlk) + c) * (SR * kWave) + (v * R + u) * kWave + k % kWave] = w[src + a * kBlk + b];
+    } else {
+        tile[a][b] = w[src + a * kBlk + b];
+        __syncthreads();
+        // produced channel = c (fast index b), reduced channel = k (a)
+        const int c = cb * kBlk + b, k = kb * kBlk + a;
+        wl[((size_t)(c / kWave) * (KB * kBlk) + k) * (SR * kWave) + ((S - 1 - v) * R + (R - 1 - u)) * kWave + c % kWave] = tile[b][a];
+    }
+}
+
+}  // namespace
+
+size_t fwd_sparse_filter_bytes(const Geom &g)
+{
+    return (size_t)ceil_div(g.Ko, kWave) * kWave * g.Ci * g.S * g.R * sizeof(float);
+}
+
+hipError_t launch_wave_filters(const Geom &g, bool transpose, const float *w, float *wl, hipStream_t s)
+{
+    const int KB = (transpose ? g.Ci : g.Ko) / kBlk, CB = (transpose ? g.Ko : g.Ci) / kBlk;     // of the layer
+    const long long blocks = (long long)KB * CB * g.S * g.R;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (transpose)
+        hipLaunchKernelGGL(wave_filters_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl);
+    else
+        hipLaunchKernelGGL(wave_filters_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl);
+    return hipGetLastError();
 }
 
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)

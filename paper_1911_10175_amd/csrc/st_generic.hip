@@ -204,24 +204,6 @@ __global__ void clear_counters_kernel(unsigned *c)
     c[threadIdx.x] = 0u;
 }
 
-// wt[cb][kb][S-1-v][R-1-u][ki][ci] = w[kb][cb][v][u][ci][ki]
-__global__ __launch_bounds__(256) void transpose_filters_kernel(int KB, int CB, int S, int R,
-                                                                const float *__restrict__ w,
-                                                                float *__restrict__ wt)
-{
-    __shared__ float tile[kBlk][kBlk + 1];
-    int t = blockIdx.x;
-    const int u = t % R; t /= R;
-    const int v = t % S; t /= S;
-    const int cb = t % CB;
-    const int kb = t / CB;
-    const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
-    tile[a][b] = w[flt_off(kb, cb, v, u, CB, S, R) + a * kBlk + b];      // a = ci, b = ki
-    __syncthreads();
-    // destination block [cb][kb][S-1-v][R-1-u], element [ki = a][ci = b]
-    wt[flt_off(cb, kb, S - 1 - v, R - 1 - u, KB, S, R) + a * kBlk + b] = tile[b][a];
-}
-
 inline void out_dims(const st_conv_desc &d, int &OH, int &OW)
 {
     OH = (d.H + 2 * d.pad_h - d.S) / d.stride_h + 1;
@@ -296,14 +278,6 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
         hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 1024 ? sampled : 1024)), dim3(256), 0, s, t[i],
                            n[i], (unsigned)stride, sampled, counters + 2 * i);
     }
-    return hipGetLastError();
-}
-
-hipError_t launch_transpose_filters(const st_conv_desc &d, const float *w, float *wt, hipStream_t s)
-{
-    const int KB = d.K / kBlk, CB = d.C / kBlk;
-    dim3 grid(KB * CB * d.S * d.R);
-    hipLaunchKernelGGL(transpose_filters_kernel, grid, dim3(256), 0, s, KB, CB, d.S, d.R, w, wt);
     return hipGetLastError();
 }
 

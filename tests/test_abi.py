@@ -64,7 +64,14 @@ def test_validation_happens_on_the_host():
 
 def test_workspace_query_and_rejection():
     d = st.ConvDesc(16, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_workspace_bytes(d, st.ST_PASS_FWD) == 0
+    # the tiled zero-skipping FWD / BWI read a copy of the filters in wavefront order: the produced
+    # channels (K for FWD, C for BWI) rounded up to whole groups of 64
+    assert st.st_conv_workspace_bytes(d, st.ST_PASS_FWD) == 256 * 256 * 9 * 4
+    odd = st.ConvDesc(2, 48, 80, 12, 12, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_workspace_bytes(odd, st.ST_PASS_FWD) == 128 * 48 * 9 * 4
+    assert st.st_conv_workspace_bytes(odd, st.ST_PASS_BWI) == 64 * 80 * 9 * 4
+    assert st.st_conv_fwd(d, 256, 256, 256, ws=None, check=False) == 4
+    assert st.st_conv_fwd(d, 256, 256, 256, ws=4096 + 64, ws_bytes=1 << 30, check=False) == 4
     for dense in (False, True):
         need = st.st_conv_workspace_bytes(d, st.ST_PASS_BWI, dense)
         if need:
@@ -97,6 +104,7 @@ def test_workspace_query_and_rejection():
         assert fn(d, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
     # shapes served by the generic kernel need none
     assert st.st_conv_workspace_bytes(st.ConvDesc(1, 16, 16, 8, 8, 5, 5, 1, 1, 2, 2), st.ST_PASS_BWW_DY) == 0
+    assert st.st_conv_workspace_bytes(st.ConvDesc(1, 16, 16, 8, 8, 5, 5, 1, 1, 2, 2), st.ST_PASS_FWD) == 0
     assert st.st_conv_workspace_bytes(d, 7) == 0
 
 
