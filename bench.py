@@ -27,8 +27,8 @@ PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
 
 # HBM traffic per launch of the dominant kernel (fwd_sparse_kernel on this workload) from two
 # rocprofv3 --pmc runs, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 (factors from a 256 MiB copy of known
-# size): 75231.9 KiB * 2 + 78398.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = int((47496.8 * 2.0 + 50176.0) * 1024)
+# size): 47685.5 KiB * 2 + 50176.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = int((47685.5 * 2.0 + 50176.0) * 1024)
 
 
 def write_config_table(path, st, stgen, torch, dev, stream):
@@ -265,14 +265,15 @@ def main():
     del xdead, xdead_h
 
     # ---- roofline of the dominant kernel ----
-    # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy), so the
-    # event time of st_conv_fwd is that kernel's launch duration.  Algorithmic work per launch:
-    # F * (1 - realised zero fraction) flops on the vector ALUs.
+    # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy) behind a
+    # filter-copy launch of about 5 us (1-2 % of the call), so the event time of st_conv_fwd is that
+    # kernel's launch duration plus the copy: the fraction below is the slightly pessimistic one.
+    # Algorithmic work per launch: F * (1 - realised zero fraction) flops on the vector ALUs.
     dom = max(passes, key=lambda k: passes[k]["sparse_avg_ms"])
     fwd_avg_ms = passes["fwd"]["sparse_avg_ms"]
     achieved = F * (1 - px) / (fwd_avg_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4,4,1,1,0> (st_conv_fwd; st_conv_bwi runs the same kernel on dy)",
+        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4,4,1,1,0> (st_conv_fwd incl. its 5 us filter copy; st_conv_bwi runs the same kernel on dy)",
         "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_FP32_VECTOR, 4),
         "peak_unpacked_fma": PEAK_FP32_FMA, "frac_of_unpacked_fma_peak": round(achieved / PEAK_FP32_FMA, 4),

@@ -82,7 +82,8 @@ enum {
  *   x  in   [N][C/16][H][W][16]           w  in  [K/16][C/16][S][R][16][16]
  *   y  out  [N][K/16][OH][OW][16]
  *   ws / ws_bytes: workspace of at least st_conv_workspace_bytes(desc, ST_PASS_FWD, dense)
- *                  bytes (may be NULL when that is 0).
+ *                  bytes (may be NULL when that is 0).  The tiled kernels read the filters from a
+ *                  copy in their own order which they write there first, on every call.
  */
 st_status st_conv_fwd(const st_conv_desc *desc, const float *x, const float *w, float *y,
                       void *ws, size_t ws_bytes, void *hip_stream);

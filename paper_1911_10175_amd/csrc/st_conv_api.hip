@@ -360,6 +360,6 @@ const char *st_status_str(st_status status)
     }
 }
 
-const char *st_conv_version(void) { return "0.4"; }
+const char *st_conv_version(void) { return "0.5"; }
 
 }  // extern "C"
