@@ -161,28 +161,42 @@ __global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int 
 // Zero statistics for the operand choice of BWW (SparseTrain Sec. 5.3 picks the operand with the
 // higher average sparsity): counts the elements equal to zero in a sample of a tensor, one block of
 // 1024 consecutive floats out of every `stride` blocks, and adds {zeros, elements looked at} to
-// out[0], out[1] with integer atomics (order-independent, hence deterministic).
+// out[0], out[1] with one 64-bit integer atomic per workgroup (order-independent, hence
+// deterministic; the sample is capped at 2^30 elements, so the low word never carries into the high).
+// Atomics to one address are serialised by the memory system at about 25 ns each: a launch uses at
+// most 256 workgroups, and each keeps four loads in flight per thread instead.
 __global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restrict__ t, size_t n, unsigned stride,
                                                           size_t sampled_blocks, unsigned *__restrict__ out)
 {
     __shared__ unsigned wz[4], wn[4];
     unsigned zeros = 0, seen = 0;
-    for (size_t b = blockIdx.x; b < sampled_blocks; b += gridDim.x) {
-        const size_t base = b * stride * 1024 + threadIdx.x * 4;
-        if (base + 3 < n) {                              // tensors are 64-byte aligned: one 16-byte load
-            const float4 v = *reinterpret_cast<const float4 *>(t + base);
-            zeros += (v.x == 0.f ? 1u : 0u) + (v.y == 0.f ? 1u : 0u) + (v.z == 0.f ? 1u : 0u) + (v.w == 0.f ? 1u : 0u);
-            seen += 4u;
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (base + j < n) {
-                    zeros += t[base + j] == 0.f ? 1u : 0u;
-                    seen += 1u;
-                }
+    constexpr int UN = 4;
+    for (size_t b0 = blockIdx.x; b0 < sampled_blocks; b0 += (size_t)gridDim.x * UN) {
+        float4 v[UN];
+        bool full[UN];
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const size_t b = b0 + (size_t)i * gridDim.x;
+            const size_t base = b * stride * 1024 + threadIdx.x * 4;
+            full[i] = b < sampled_blocks && base + 3 < n;      // tensors are 64-byte aligned: one 16-byte load
+            v[i] = full[i] ? *reinterpret_cast<const float4 *>(t + base) : make_float4(1.f, 1.f, 1.f, 1.f);
+        }
+#pragma unroll
+        for (int i = 0; i < UN; ++i) {
+            const size_t b = b0 + (size_t)i * gridDim.x;
+            const size_t base = b * stride * 1024 + threadIdx.x * 4;
+            if (full[i]) {
+                zeros += (v[i].x == 0.f ? 1u : 0u) + (v[i].y == 0.f ? 1u : 0u) + (v[i].z == 0.f ? 1u : 0u) + (v[i].w == 0.f ? 1u : 0u);
+                seen += 4u;
+            } else if (b < sampled_blocks) {
+                for (int j = 0; j < 4; ++j)
+                    if (base + j < n) {
+                        zeros += t[base + j] == 0.f ? 1u : 0u;
+                        seen += 1u;
+                    }
+            }
         }
     }
-    // wavefront sums, workgroup sum, then one pair of atomics per workgroup (a few hundred in all:
-    // atomics to one address are serialised by the memory system)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         zeros += __shfl_down(zeros, off);
@@ -194,8 +208,8 @@ __global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restric
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        atomicAdd(out, wz[0] + wz[1] + wz[2] + wz[3]);
-        atomicAdd(out + 1, wn[0] + wn[1] + wn[2] + wn[3]);
+        const unsigned long long z = wz[0] + wz[1] + wz[2] + wz[3], m = wn[0] + wn[1] + wn[2] + wn[3];
+        atomicAdd(reinterpret_cast<unsigned long long *>(out), z | (m << 32));      // out is 8-byte aligned
     }
 }
 
@@ -275,7 +289,7 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
         size_t stride = blocks < 64 ? 1 : 8;
         while ((blocks + stride - 1) / stride > (1u << 20)) stride *= 2;
         const size_t sampled = (blocks + stride - 1) / stride;
-        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 1024 ? sampled : 1024)), dim3(256), 0, s, t[i],
+        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 256 ? sampled : 256)), dim3(256), 0, s, t[i],
                            n[i], (unsigned)stride, sampled, counters + 2 * i);
     }
     return hipGetLastError();
