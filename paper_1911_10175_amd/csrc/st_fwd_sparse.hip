@@ -39,7 +39,6 @@ struct FwdSparseCfg {
     static constexpr int HP = HH * HW;
     static constexpr int NXV = (HP + 63) / 64;              // registers holding one channel of the halo
     static constexpr int PST = ((HP + 7) / 8) * 8 + 4;      // LDS pixel stride, = 4 (mod 8), >= HP rounded up to 4
-    static constexpr int WAVES = 4;
     static constexpr int KT = 64 * KPL;                     // output channels per wavefront
 };
 
@@ -47,7 +46,7 @@ struct FwdSparseCfg {
 // partial tiles are added through LDS at the end (in a fixed order).  CS > 1 multiplies the
 // number of wavefronts of a layer with few tiles without shrinking the tile.
 template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD = 1, int SU = 1, int OFF = 0>
-__global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
+__global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
                                                          const float *__restrict__ f,
                                                          float *__restrict__ out,
                                                          int tiles_w, int tiles_h, int ktiles, int total,
@@ -56,7 +55,8 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
     if (form_deselected(g.sel, g.want, g.thr)) return;          // uniform over the grid, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST;
-    __shared__ __attribute__((aligned(16))) float lds_all[Cfg::WAVES][kBlk * PST];
+    constexpr int WAVES = CS > 4 ? CS : 4;          // wavefronts per workgroup
+    __shared__ __attribute__((aligned(16))) float lds_all[WAVES][kBlk * PST];
 
     // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256, MINW) void fwd_sparse_kernel(Geom g, const flo
     // other.  Every XCD gets a contiguous range of pixel tiles and walks it tile by tile, all
     // output-channel tiles of a pixel tile first: the input halo shared by those workgroups, and the
     // halo columns shared with the next pixel tile, are fetched into that L2 once.
-    constexpr int TPW = Cfg::WAVES / CS;            // tasks (pixel tiles) per workgroup
+    constexpr int TPW = WAVES / CS;                 // tasks (pixel tiles) per workgroup
     const int xcd = blockIdx.x % 8, seq = blockIdx.x / 8;
     const int kt = seq % ktiles;
     const int tile = (xcd * slots_per_xcd + seq / ktiles) * TPW + wave / CS;
@@ -334,32 +334,42 @@ hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out,
     const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
     const int ktiles = ceil_div(g.Ko, Cfg::KT);
     const long long tiles = (long long)tiles_w * tiles_h * g.N;
-    constexpr int per_wg = Cfg::WAVES / CS;
+    constexpr int waves = CS > 4 ? CS : 4;
+    constexpr int per_wg = waves / CS;
     const long long slots = (tiles + per_wg - 1) / per_wg;             // workgroups per output-channel tile
     const long long slots_per_xcd = (slots + 7) / 8;
     const long long blocks = slots_per_xcd * 8 * ktiles;
     if (tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS, SD, SU, OFF>), dim3((unsigned)blocks), dim3(256), 0, s,
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS, SD, SU, OFF>), dim3((unsigned)blocks), dim3(64 * waves), 0, s,
                        g, in, f, out, tiles_w, tiles_h, ktiles, (int)tiles, (int)slots_per_xcd);
     return hipGetLastError();
 }
 
-// Picks the channel split: layers with few tiles get 2 or 4 wavefronts per task so that the chip
-// (1024 SIMDs x 4 resident wavefronts) is filled and the tail is short.  ST_FWD_SPARSE_CS
-// overrides (tuning aid).
+// Picks the channel split: layers with few tiles get 2, 4, 8 or 16 wavefronts per task so that the chip
+// (1024 SIMDs x 4 resident wavefronts) is filled and the tail is short: a wavefront walks its share
+// of the input channels one after the other, about 1.7 us per channel, so a launch that leaves
+// half the wavefront slots empty is as slow as one that fills them.  ST_FWD_SPARSE_CS overrides
+// (tuning aid).
 template <int R, int S, int TH, int TW, int KPL, int MINW, int SD = 1, int SU = 1, int OFF = 0>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
     const long long tasks = (long long)ceil_div(g.Wo, TW) * ceil_div(g.Ho, TH) * ceil_div(g.Ko, Cfg::KT) * g.N;
     const int CiB = g.Ci / kBlk;
+    constexpr bool deep = R == 3 && SD == 1 && SU == 1;     // 8- and 16-way splits: unit-stride 3x3 only
     int cs = 1;
     if (CiB >= 4 && CiB % 2 == 0) cs = 2;
     if ((CiB >= 16 || tasks < 3072) && CiB % 4 == 0) cs = 4;
+    if (deep && tasks <= 512 && CiB % 8 == 0) cs = 8;
+    if (deep && tasks <= 256 && CiB % 16 == 0) cs = 16;
     const char *env = getenv("ST_FWD_SPARSE_CS");
     if (env) {
         const int e = atoi(env);
-        if ((e == 1 || e == 2 || e == 4) && CiB % e == 0) cs = e;
+        if ((e == 1 || e == 2 || e == 4 || (deep && (e == 8 || e == 16))) && CiB % e == 0) cs = e;
+    }
+    if constexpr (deep) {
+        if (cs == 16) return launch_cs<R, S, TH, TW, KPL, MINW, 16, SD, SU, OFF>(g, in, f, out, s);
+        if (cs == 8) return launch_cs<R, S, TH, TW, KPL, MINW, 8, SD, SU, OFF>(g, in, f, out, s);
     }
     if (cs == 4) return launch_cs<R, S, TH, TW, KPL, MINW, 4, SD, SU, OFF>(g, in, f, out, s);
     if (cs == 2) return launch_cs<R, S, TH, TW, KPL, MINW, 2, SD, SU, OFF>(g, in, f, out, s);
@@ -391,7 +401,14 @@ unsigned fwd_sparse_threshold(const Geom &g)
     if (g.R == 1) return g.Ko % 256 == 0 ? 900 : 1001;
     if (g.sw == 2) return 800;
     if (g.uw == 2) return 500;
-    return g.Ko % 128 == 0 ? 400 : 620;
+    // launches with so few tasks that the reduction is split 16 ways (launch_fwd_sparse): the dense
+    // form has no such split and leaves most of the chip idle; the zero-skipping form wins at any
+    // sparsity (1.2-1.6x at 0 % zeros on 7x7 and 14x14 layers)
+    const bool wide = g.Ko % 128 == 0, seven = g.Wo % 8 != 0 && g.Wo % 7 == 0;
+    const long long tasks = (long long)ceil_div(g.Wo, seven ? 7 : 8) * ceil_div(g.Ho, wide ? 4 : 8) *
+                            ceil_div(g.Ko, wide ? 128 : 64) * g.N;
+    if (tasks <= 256 && (g.Ci / kBlk) % 16 == 0) return 0;
+    return wide ? 400 : 620;
 }
 
 namespace {

@@ -57,6 +57,11 @@ SMALL = [
     ("3x3_c96_split2", Geom(1, 96, 128, 9, 9, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
     ("3x3_c64_k64_split4", Geom(2, 64, 64, 10, 13, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
     ("3x3_c256_k128_split4", Geom(1, 256, 128, 6, 7, 3, 3, 1, 1, 1, 1), 0.6, 0.6),
+    # 8 and 16 shares (launches with few tasks): FWD reduces C, BWI reduces K; two- and one-channel-per-lane tiles
+    ("3x3_c128_k256_split8", Geom(2, 128, 256, 9, 10, 3, 3, 1, 1, 1, 1), 0.5, 0.5),
+    ("3x3_c384_k64_split8", Geom(1, 384, 64, 7, 7, 3, 3, 1, 1, 1, 1), 0.5, 0.6),
+    ("3x3_c512_k256_split16", Geom(1, 512, 256, 5, 9, 3, 3, 1, 1, 1, 1), 0.6, 0.5),
+    ("3x3_c256_k64_split16_pad2", Geom(2, 256, 64, 6, 6, 3, 3, 1, 1, 2, 2), 0.5, 0.5),
     # other paddings of the 3x3 fast path
     ("3x3_pad0", Geom(2, 32, 64, 12, 14, 3, 3, 1, 1, 0, 0), 0.5, 0.5),
     ("3x3_pad2_1", Geom(1, 32, 64, 9, 10, 3, 3, 1, 1, 2, 1), 0.5, 0.5),
@@ -120,6 +125,16 @@ def test_sparse_equals_dense_control_and_is_deterministic():
         assert np.array_equal(a, b), "two runs of the sparse kernel differ"
         c = fn(True)
         assert np.allclose(a, c, rtol=1e-3, atol=1e-4)
+
+
+@pytest.mark.parametrize("cs", [1, 2, 4, 8, 16])
+def test_fwd_bwi_channel_split_override(cs, monkeypatch):
+    """Every channel split of the zero-skipping FWD / BWI kernel (normally chosen from the number of
+    tasks of the launch; ST_FWD_SPARSE_CS forces one) gives the oracle's result on ragged tiles."""
+    g = Geom(2, 256, 256, 10, 13, 3, 3, 1, 1, 1, 1)
+    x, w, dy = synth(g, 0.6, 0.5, seed=31 + cs)
+    monkeypatch.setenv("ST_FWD_SPARSE_CS", str(cs))
+    check_all_passes_full(g, x, w, dy, f"split {cs}", passes=("fwd", "bwi"), variants=(False,))
 
 
 BWW_DY_SHAPES = [
@@ -243,6 +258,18 @@ def test_fwd_bwi_auto_pick_the_form_by_sparsity(p, form):
     counters = L.auto_ws[:2].cpu().numpy().view(np.uint32)
     assert tuple(int(c) for c in counters) == sampled_zero_counts(st.pack_activations(dy))
     assert np.array_equal(got, L.bwi(form))
+
+
+def test_fwd_bwi_auto_small_launch_always_zero_skipping():
+    """A unit-stride 3x3 launch of at most 256 tasks whose reduction splits 16 ways: only the
+    zero-skipping form spreads over the chip, so it is taken even at 10 % zeros."""
+    g = Geom(1, 256, 256, 7, 7, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_sparse_threshold(desc_of(g), st.ST_PASS_FWD) == 0
+    x, w, dy = synth(g, 0.1, 0.1, seed=63)
+    L = DeviceLayer(g, x, w, dy)
+    assert not np.array_equal(L.fwd(False), L.fwd(True)), "forms indistinguishable: test is void"
+    assert np.array_equal(L.fwd("auto"), L.fwd(False))
+    assert np.array_equal(L.bwi("auto"), L.bwi(False))
 
 
 def test_fwd_auto_1x1_never_takes_the_narrow_sparse_form():
