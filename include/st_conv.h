@@ -136,7 +136,10 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
  * zeros in a sample of x and of dy (one block of 1024 elements in eight); then both forms above are
  * enqueued, and the one the counts do not select returns at once: x is tested unless dy has the
  * strictly larger zero fraction.  Same tensors, same result, no host synchronisation; the cost is
- * the sampling pass (about 1/8 of x and dy is read once more) and one empty launch.  Stride-2 3x3
+ * the sampling pass (about 1/8 of x and dy is read once more) and the empty launches.  Where tiled
+ * kernels exist, the dense form (st_conv_bww_dense) is the third candidate: it runs when even the
+ * sparser operand has fewer zeros than the measured break-even, 35 % for 3x3 and 90 % for 1x1
+ * layers (Sec. 5.3 combines the kernels with dense ones layer by layer).  Stride-2 3x3
  * layers are the exception: there dy is always tested, without sampling (x has four times the
  * elements and each feeds fewer taps, Sec. 3.3, so that form is the faster one at any sparsity).
  * Workspace: st_conv_workspace_bytes(desc, ST_PASS_BWW_AUTO, 0).

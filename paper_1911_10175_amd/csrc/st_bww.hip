@@ -35,7 +35,8 @@ struct BwwArgs {
     int splits;                // partial sums; gridDim.x
     int cgroups;               // ceil(C/64)
     // operand selection on the device (st_conv_bww_auto): when sel is set, the launch does nothing
-    // unless the sampled zero counts pick the operand this launch tests (want: 0 = x, 1 = dy)
+    // unless the sampled zero counts pick the form this launch computes (want: 0 = tests x, 1 = tests dy,
+    // 2 = dense)
     const unsigned *sel;
     int want;
 };
@@ -232,6 +233,7 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
                                                         float *__restrict__ part)
 {
     using Cfg = BwwCfg<R, S, TH, TW, PSTEP>;
+    if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
     static_assert(TW % 2 == 0, "pixel pairs must not straddle rows");
     __shared__ __attribute__((aligned(16))) float dyT[TP * 64];
@@ -327,6 +329,7 @@ __global__ __launch_bounds__(256) void pw_bww_dense_kernel(BwwArgs A, const floa
                                                            const float *__restrict__ dy,
                                                            float *__restrict__ part)
 {
+    if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
     constexpr int P = kPwP, CW = 128;                   // channels of either operand per workgroup
     __shared__ __attribute__((aligned(16))) float xs[P * CW];
     __shared__ __attribute__((aligned(16))) float ds[P * CW];
@@ -825,10 +828,11 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
 }
 
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                            float *ws, hipStream_t s)
+                            float *ws, hipStream_t s, const unsigned *sel)
 {
     if (bww_s2(d)) {
-        const BwwArgs A2 = make_args(d, kS2TH, kS2TW, false);
+        BwwArgs A2 = make_args(d, kS2TH, kS2TW, false);
+        A2.sel = sel; A2.want = 2;
         dim3 grid2(A2.splits, ceil_div(d.K, 64) * A2.cgroups);
         hipLaunchKernelGGL((bww_dense_kernel<3, 3, kS2TH, kS2TW, 2>), grid2, dim3(256), 0, s, A2, x, dy,
                            A2.splits == 1 ? dw : ws);
@@ -836,19 +840,31 @@ hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *
         return err != hipSuccess ? err : reduce(d, A2, ws, dw, s);
     }
     if (d.R == 1) {
-        const BwwArgs A1 = make_args_pw(d, 128, 128);
+        BwwArgs A1 = make_args_pw(d, 128, 128);
+        A1.sel = sel; A1.want = 2;
         dim3 grid1(A1.splits, ceil_div(d.K, 128) * A1.cgroups);
         hipLaunchKernelGGL(pw_bww_dense_kernel, grid1, dim3(256), 0, s, A1, x, dy, A1.splits == 1 ? dw : ws);
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A1, ws, dw, s);
     }
-    const BwwArgs A = make_args(d, kDenseTH, kDenseTW, false);
+    BwwArgs A = make_args(d, kDenseTH, kDenseTW, false);
+    A.sel = sel; A.want = 2;
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
     hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), grid, dim3(256), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
+}
+
+// Measured on the layer shapes of the paper's Table 1: the 3x3 zero-skipping forms pass the dense one at 30-35 % zeros;
+// a 1x1 layer saves at most K/64 (or C/64) multiply-adds per zero and stays behind the matrix cores up
+// to about 90 % zeros.  (Stride-2 layers never get here: their dy-testing form beats the dense one
+// even without zeros.)
+unsigned bww_sparse_threshold(const st_conv_desc &d)
+{
+    if (!bww_fast_supported(d)) return 0;           // generic kernels: the test only ever removes work
+    return d.R == 1 ? 900 : 350;
 }
 
 }  // namespace st

@@ -68,13 +68,17 @@ __device__ __forceinline__ bool form_deselected(const unsigned *sel, int want, u
     return (sparse ? 0 : 1) != want;
 }
 
-// BWW operand choice (st_conv_bww_auto): sel = {zeros of x in the sample, sample size of x, zeros of dy,
-// sample size of dy}; dy (want = 1) is tested when its zero fraction is strictly larger
+// BWW form choice (st_conv_bww_auto): sel = {zeros of x in the sample, sample size of x, zeros of dy,
+// sample size of dy, dense threshold in per mille}.  dy (want = 1) is tested when its zero fraction
+// is strictly larger, else x (want = 0); when even the sparser operand has fewer zeros than the
+// threshold, the dense form (want = 2) runs instead (threshold 0: never)
 __device__ __forceinline__ bool deselected(const unsigned *sel, int want)
 {
     if (!sel) return false;
     const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
-    return (dy_sparser ? 1 : 0) != want;
+    const unsigned zb = dy_sparser ? sel[2] : sel[0], nb = dy_sparser ? sel[3] : sel[1];
+    const bool dense = (unsigned long long)zb * 1000ull < (unsigned long long)sel[4] * nb;
+    return (dense ? 2 : (dy_sparser ? 1 : 0)) != want;
 }
 #endif
 
@@ -92,9 +96,10 @@ hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float
                               bool sparse, hipStream_t s, const unsigned *sel = nullptr);
 hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                                  hipStream_t s, const unsigned *sel = nullptr);
-// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of one block in eight); dy may be null
+// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of one block in eight; dy may be null);
+// counters[4] = dense_thr, the per-mille zero fraction below which st_conv_bww_auto runs its dense form
 hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
-                              hipStream_t s);
+                              hipStream_t s, unsigned dense_thr = 0);
 // zero fraction (per mille) of the tested operand from which the zero-skipping FWD/BWI form beats the
 // dense one for this geometry (measured; 1001 = never)
 unsigned fwd_sparse_threshold(const Geom &g);
@@ -132,6 +137,8 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
                                 float *ws, hipStream_t s, const unsigned *sel = nullptr);
 size_t bww_dense_workspace(const st_conv_desc &d);
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
-                            float *ws, hipStream_t s);
+                            float *ws, hipStream_t s, const unsigned *sel = nullptr);
+// zero fraction (per mille) of the sparser operand below which the dense BWW beats both zero-skipping forms
+unsigned bww_sparse_threshold(const st_conv_desc &d);
 
 }  // namespace st

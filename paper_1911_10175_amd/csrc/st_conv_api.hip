@@ -99,7 +99,9 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
         if (dense) return workspace_bytes(d, o, ST_PASS_BWW, true);
         // 256 bytes of counters, then the partial sums of whichever form runs
         const size_t a = workspace_bytes(d, o, ST_PASS_BWW, false), b = workspace_bytes(d, o, ST_PASS_BWW_DY, false);
-        return kCounterBytes + (a > b ? a : b);
+        const size_t c = workspace_bytes(d, o, ST_PASS_BWW, true);
+        const size_t m = a > b ? a : b;
+        return kCounterBytes + (m > c ? m : c);
     }
     default:
         return 0;
@@ -259,13 +261,17 @@ st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, f
     if (d->stride_w == 2 && d->stride_h == 2 && st::bww_dy_fast_supported(*d))
         return dev(st::launch_bww_sparse_dy(*d, x, dy, dw, part, s));
     const size_t nx = (size_t)d->N * d->C * d->H * d->W, ny = (size_t)d->N * d->K * o.OH * o.OW;
-    if (st::launch_zero_sample(x, nx, dy, ny, sel, s) != hipSuccess) return ST_ERR_DEVICE;
+    // the dense form takes part in the choice where tiled kernels exist for all three
+    const bool tiled = st::bww_fast_supported(*d) && st::bww_dy_fast_supported(*d);
+    const unsigned dense_thr = tiled ? st::bww_sparse_threshold(*d) : 0;
+    if (st::launch_zero_sample(x, nx, dy, ny, sel, s, dense_thr) != hipSuccess) return ST_ERR_DEVICE;
     hipError_t e = st::bww_fast_supported(*d) ? st::launch_bww_sparse(*d, x, dy, dw, part, s, sel)
                                               : st::launch_generic_bww(*d, x, dy, dw, true, s, sel);
     if (e != hipSuccess) return ST_ERR_DEVICE;
     e = st::bww_dy_fast_supported(*d) ? st::launch_bww_sparse_dy(*d, x, dy, dw, part, s, sel)
                                       : st::launch_generic_bww_dy(*d, x, dy, dw, s, sel);
-    return dev(e);
+    if (e != hipSuccess || dense_thr == 0) return dev(e);
+    return dev(st::launch_bww_dense(*d, x, dy, dw, part, s, sel));
 }
 
 }  // namespace

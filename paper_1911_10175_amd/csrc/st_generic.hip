@@ -213,9 +213,9 @@ __global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restric
     }
 }
 
-__global__ void clear_counters_kernel(unsigned *c)
+__global__ void clear_counters_kernel(unsigned *c, unsigned dense_thr)
 {
-    c[threadIdx.x] = 0u;
+    c[threadIdx.x] = threadIdx.x < 4 ? 0u : dense_thr;
 }
 
 inline void out_dims(const st_conv_desc &d, int &OH, int &OW)
@@ -276,9 +276,9 @@ hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const fl
 }
 
 hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
-                              hipStream_t s)
+                              hipStream_t s, unsigned dense_thr)
 {
-    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(4), 0, s, counters);
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(5), 0, s, counters, dense_thr);
     const float *t[2] = {x, dy};
     const size_t n[2] = {nx, ny};
     for (int i = 0; i < 2; ++i) {

@@ -91,9 +91,10 @@ def test_workspace_query_and_rejection():
         assert need >= dd.K * dd.C * 9 * 4 and need % (dd.K * dd.C * 9 * 4) == 0
         assert st.st_conv_bww_dy(dd, 256, 256, 256, ws=None, check=False) == 4
         assert st.st_conv_bww_dy(dd, 256, 256, 256, ws=4096, ws_bytes=need - 1, check=False) == 4
-        # the self-selecting form: counters plus the larger of the two
+        # the self-selecting form: counters plus the largest of the three forms it chooses from
         auto = st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW_AUTO)
-        assert auto == 256 + max(need, st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW))
+        assert auto == 256 + max(need, st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW),
+                                 st.st_conv_workspace_bytes(dd, st.ST_PASS_BWW, True))
         assert st.st_conv_bww_auto(dd, 256, 256, 256, ws=4096, ws_bytes=auto - 1, check=False) == 4
     # FWD / BWI with the form chosen on the device: counters + both forms' workspaces
     for pa, pb, fn in ((st.ST_PASS_FWD_AUTO, st.ST_PASS_FWD, st.st_conv_fwd_auto),

@@ -243,6 +243,13 @@ def test_bww_auto_selects_the_sparser_operand(g, px, pdy):
     if px != pdy:
         assert (zdy * nx > zx * ndy) == (pdy > px)
     assert np.array_equal(got, L.bww("auto")), "two runs differ"
+    # which form ran: the one testing the sparser operand, or, where all three forms are tiled, the dense
+    # one when even that operand has fewer zeros than the break-even (35 % for 3x3, 90 % for 1x1)
+    if g.R == 5:
+        return
+    best = max(px, pdy)
+    form = True if best < (0.9 if g.R == 1 else 0.35) else ("dy" if pdy > px else False)
+    assert np.array_equal(got, L.bww(form)), f"expected the form {form!r}"
 
 
 @pytest.mark.parametrize("p,form", [(0.1, True), (0.9, False)])
