@@ -44,7 +44,9 @@ struct FwdSparseCfg {
 
 // CS = number of wavefronts that share one task, each reducing 1/CS of the input channels; their
 // partial tiles are added through LDS at the end (in a fixed order).  CS > 1 multiplies the
-// number of wavefronts of a layer with few tiles without shrinking the tile.
+// number of wavefronts of a layer with few tiles without shrinking the tile.  A workgroup has
+// max(4, CS) wavefronts, each with its own staging region (4.3 KB for 4x8 tiles, 6.8 KB for 8x8):
+// up to 108 KB of the 160 KB a gfx950 workgroup may use.
 template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD = 1, int SU = 1, int OFF = 0>
 __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
                                                          const float *__restrict__ f,
