@@ -62,8 +62,9 @@ def write_config_table(path, st, stgen, torch, dev, stream):
         return ts[len(ts) // 2]
 
     rows = []
+    totals = {}                     # cfg -> [sparse, dense, auto, best] summed over its rows (us)
 
-    def run(cfg, L, px, pdy):
+    def run(cfg, L, px, pdy, group=None):
         d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, L.stride, L.stride, L.pad, L.pad)
         x = relu_sparse((L.N, L.C // 16, L.H, L.W, 16), px)
         dy = masked((L.N, L.K // 16, L.OH, L.OW, 16), pdy)
@@ -76,24 +77,31 @@ def write_config_table(path, st, stgen, torch, dev, stream):
             n = st.st_conv_workspace_bytes(d, p, dn)
             return torch.empty(max(n // 4, 1), device=dev) if n else None
 
-        for name, fs, fd, a, b, o, pi, z in (("FWD", st.st_conv_fwd, st.st_conv_fwd_dense, x, w, y, 0, zx),
-                                             ("BWI", st.st_conv_bwi, st.st_conv_bwi_dense, dy, w, dx, 1, zdy),
-                                             ("BWW", st.st_conv_bww, st.st_conv_bww_dense, x, dy, dw, 2, zx)):
-            wss, wsd = ws(pi, False), ws(pi, True)
+        for name, fs, fd, fa, a, b, o, pi, pa, z in (
+                ("FWD", st.st_conv_fwd, st.st_conv_fwd_dense, st.st_conv_fwd_auto, x, w, y, 0, st.ST_PASS_FWD_AUTO, zx),
+                ("BWI", st.st_conv_bwi, st.st_conv_bwi_dense, st.st_conv_bwi_auto, dy, w, dx, 1, st.ST_PASS_BWI_AUTO, zdy),
+                ("BWW", st.st_conv_bww, st.st_conv_bww_dense, st.st_conv_bww_auto, x, dy, dw, 2, st.ST_PASS_BWW_AUTO, zx)):
+            wss, wsd, wsa = ws(pi, False), ws(pi, True), ws(pa, False)
             ts = timeit(lambda: fs(d, a, b, o, wss, stream))
             td = timeit(lambda: fd(d, a, b, o, wsd, stream))
+            ta = timeit(lambda: fa(d, a, b, o, wsa, stream))
+            best = min(ts, td)
             eff = d.flops / ts / 1e9
             label = f"{L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S}" + (f"/{L.stride}" if L.stride != 1 else "") + f" N={L.N}"
             rows.append(f"| {cfg} | {label} | {name} | {z:.2f} | {ts * 1e3:.0f} | "
                         f"{td * 1e3:.0f} | {eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | "
-                        f"{d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} |")
+                        f"{d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} | {ta * 1e3:.0f} |")
             if name == "BWW":       # the same tensor with the zero test on dy (st_conv_bww_dy); same dense control
                 wsy = ws(st.ST_PASS_BWW_DY, False)
                 ty = timeit(lambda: st.st_conv_bww_dy(d, a, b, o, wsy, stream))
+                best = min(best, ty)
                 effy = d.flops / ty / 1e9
                 rows.append(f"| {cfg} | {label} | BWW(dy) | {zdy:.2f} | {ty * 1e3:.0f} | {td * 1e3:.0f} | {effy:.1f} | "
                             f"{effy * (1 - zdy) / PEAK_FP32_VECTOR:.3f} | {d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | "
-                            f"{td / ty:.2f} |")
+                            f"{td / ty:.2f} | |")
+            t = totals.setdefault(group or str(cfg), [0.0, 0.0, 0.0, 0.0])
+            for i, v in enumerate((ts, td, ta, best)):
+                t[i] += v * 1e3
         del x, dy, w, y, dx, dw
 
     run(3, stgen.RESNET3_2, stgen.RESNET3_2.p_x, stgen.RESNET3_2.p_dy)
@@ -103,7 +111,7 @@ def write_config_table(path, st, stgen, torch, dev, stream):
         for L in stgen.vgg16_stack(p):
             if L.name in ("vgg3_3", "vgg4_3", "vgg5_2", "vgg5_3"):      # same shapes as 3_2, 4_2, 5_1
                 continue
-            run(5, L, p, p)
+            run(5, L, p, p, group=f"5 at {p:.0%} zeros")
     # every row of the paper's Table 1 (stride-2 and the late 1x1 layers included) at 50 % zeros
     for L in stgen.table1_layers(32, 0.5, 0.5):
         if L.name == "vgg1_2":
@@ -113,11 +121,18 @@ def write_config_table(path, st, stgen, torch, dev, stream):
         f.write("# Per-workload timings: `python bench.py --no-cpu --no-sweep --table <this file>` on one MI355X\n\n"
                 "Median of 7 launches (HIP events) per entry point; inputs drawn on the device with the benchmark's\n"
                 "distributions. config 3 = ResNet-34 block, 4 = ResNet-50 bottleneck, 5 = VGG16 stack at 0-90 % zeros,\n"
-                "T1 = every layer of the paper's Table 1 at 50 % zeros. BWW tests x, BWW(dy) tests dy.\n\n")
+                "T1 = every layer of the paper's Table 1 at 50 % zeros. BWW tests x, BWW(dy) tests dy; auto = the\n"
+                "st_conv_*_auto entry point of the pass (form chosen on the device from sampled zero counts).\n\n")
         f.write("| config | layer | pass | zeros of tested operand | sparse us | dense us | effective TFLOP/s | "
-                "executed / 157.3 (fp32 vector peak) | dense / 157.3 (MFMA peak) | speed-up |\n")
-        f.write("|---|---|---|---|---|---|---|---|---|---|\n")
+                "executed / 157.3 (fp32 vector peak) | dense / 157.3 (MFMA peak) | speed-up | auto us |\n")
+        f.write("|---|---|---|---|---|---|---|---|---|---|---|\n")
         f.write("\n".join(rows) + "\n")
+        f.write("\nSums over the rows of a config (FWD + BWI + BWW of every layer, us): what always calling the\n"
+                "zero-skipping entry points (st_conv_fwd/bwi/bww), always the dense ones, or the self-selecting ones\n"
+                "costs, and the sum of the fastest form per row (BWW(dy) included) as the lower bound of any choice.\n\n")
+        f.write("| config | zero-skipping | dense | auto | fastest form per row | dense / auto |\n|---|---|---|---|---|---|\n")
+        for cfg, t in totals.items():
+            f.write(f"| {cfg} | {t[0]:.0f} | {t[1]:.0f} | {t[2]:.0f} | {t[3]:.0f} | {t[1] / t[2]:.2f} |\n")
 
 
 def main():

@@ -206,15 +206,24 @@ st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float 
     float *ws_sparse = reinterpret_cast<float *>(p);
     float *ws_dense = reinterpret_cast<float *>(p + align256(workspace_bytes(*d, o, base, false)));
     const size_t n_act = bwi ? (size_t)d->N * d->K * o.OH * o.OW : (size_t)d->N * d->C * d->H * d->W;
-    if (st::launch_zero_sample(act, n_act, nullptr, 0, sel, s) != hipSuccess) return ST_ERR_DEVICE;
 
     Geom g = fwd_geom(*d, o);
     const bool as_corr = bwi ? bwi_as_fwd(*d, o, &g) : true;
     const bool fast_sparse = as_corr && st::fwd_sparse_supported(g);
     const bool fast_dense = as_corr && st::fwd_dense_supported(g);
-    g.sel = sel;
     g.thr = fast_sparse ? st::fwd_sparse_threshold(g) : 0;
     if (!fast_dense && fast_sparse) g.thr = 0;      // tiled zero-skipping form against a generic dense one
+    // Geometries whose answer does not depend on the data (break-even at 0: always zero-skipping;
+    // above 1000 per mille: never) go straight to that form: no sampling, no second form enqueued.
+    if (g.thr == 0 || g.thr > 1000) {
+        const bool dense = g.thr > 1000;
+        const size_t off = dense ? align256(workspace_bytes(*d, o, base, false)) : 0;
+        const size_t left = ws_bytes > kCounterBytes + off ? ws_bytes - kCounterBytes - off : 0;
+        return bwi ? run_bwi(d, act, w, out, left ? p + off : nullptr, left, stream, dense)
+                   : run_fwd(d, act, w, out, left ? p + off : nullptr, left, stream, dense);
+    }
+    if (st::launch_zero_sample(act, n_act, nullptr, 0, sel, s) != hipSuccess) return ST_ERR_DEVICE;
+    g.sel = sel;
     hipError_t e;
     // zero-skipping form
     g.want = 0;

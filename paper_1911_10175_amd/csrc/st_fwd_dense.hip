@@ -213,8 +213,10 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
 // padded with zeros to a multiple of 128.
 __global__ __launch_bounds__(256) void reformat_filters_kernel(int Ko, int Ci, int S, int R, int transpose,
                                                                const float *__restrict__ w,
-                                                               float *__restrict__ wd, size_t total)
+                                                               float *__restrict__ wd, size_t total,
+                                                               const unsigned *sel, unsigned thr)
 {
+    if (form_deselected(sel, 1, thr)) return;       // the copy of a form that will not run is not written
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     const int TAPS = S * R, CiB = Ci / kBlk;
@@ -330,7 +332,7 @@ hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w
 {
     const size_t total = fwd_dense_filter_bytes(g) / sizeof(float);
     hipLaunchKernelGGL(reformat_filters_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, g.Ko, g.Ci,
-                       g.S, g.R, transpose ? 1 : 0, w, wd, total);
+                       g.S, g.R, transpose ? 1 : 0, w, wd, total, g.sel, g.thr);
     return hipGetLastError();
 }
 

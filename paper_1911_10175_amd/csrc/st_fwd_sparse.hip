@@ -423,8 +423,10 @@ namespace {
 // the filter blocks of the LAYER, w its filters in the library layout.
 template <bool TRANSPOSE>
 __global__ __launch_bounds__(256) void wave_filters_kernel(int KB, int CB, int S, int R,
-                                                           const float *__restrict__ w, float *__restrict__ wl)
+                                                           const float *__restrict__ w, float *__restrict__ wl,
+                                                           const unsigned *sel, unsigned thr)
 {
+    if (form_deselected(sel, 0, thr)) return;       // the copy of a form that will not run is not written
     __shared__ float tile[kBlk][kBlk + 1];
     int t = blockIdx.x;
     const int u = t % R; t /= R;
@@ -459,9 +461,9 @@ hipError_t launch_wave_filters(const Geom &g, bool transpose, const float *w, fl
     const long long blocks = (long long)KB * CB * g.S * g.R;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (transpose)
-        hipLaunchKernelGGL(wave_filters_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl);
+        hipLaunchKernelGGL(wave_filters_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl, g.sel, g.thr);
     else
-        hipLaunchKernelGGL(wave_filters_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl);
+        hipLaunchKernelGGL(wave_filters_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl, g.sel, g.thr);
     return hipGetLastError();
 }
 

@@ -158,17 +158,28 @@ __global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int 
     if (active) dw[flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk + ki] = acc;
 }
 
+struct SampleArgs {
+    const float *t[2];          // x, dy (or one tensor and null)
+    size_t n[2];                // elements
+    unsigned stride[2];         // every stride-th block of 1024 elements is looked at
+    size_t sampled[2];          // number of such blocks
+};
+
 // Zero statistics for the operand choice of BWW (SparseTrain Sec. 5.3 picks the operand with the
 // higher average sparsity): counts the elements equal to zero in a sample of a tensor, one block of
 // 1024 consecutive floats out of every `stride` blocks, and adds {zeros, elements looked at} to
-// out[0], out[1] with one 64-bit integer atomic per workgroup (order-independent, hence
+// out[2 * tensor], out[2 * tensor + 1] with one 64-bit integer atomic per workgroup (order-independent, hence
 // deterministic; the sample is capped at 2^30 elements, so the low word never carries into the high).
 // Atomics to one address are serialised by the memory system at about 25 ns each: a launch uses at
 // most 256 workgroups, and each keeps four loads in flight per thread instead.
-__global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restrict__ t, size_t n, unsigned stride,
-                                                          size_t sampled_blocks, unsigned *__restrict__ out)
+// blockIdx.y selects the tensor: x and dy are sampled by one launch.
+__global__ __launch_bounds__(256) void zero_sample_kernel(SampleArgs a, unsigned *__restrict__ out)
 {
     __shared__ unsigned wz[4], wn[4];
+    const int which = blockIdx.y;
+    const float *__restrict__ t = a.t[which];
+    const size_t n = a.n[which], sampled_blocks = a.sampled[which];
+    const unsigned stride = a.stride[which];
     unsigned zeros = 0, seen = 0;
     constexpr int UN = 4;
     for (size_t b0 = blockIdx.x; b0 < sampled_blocks; b0 += (size_t)gridDim.x * UN) {
@@ -209,7 +220,7 @@ __global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restric
     __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned long long z = wz[0] + wz[1] + wz[2] + wz[3], m = wn[0] + wn[1] + wn[2] + wn[3];
-        atomicAdd(reinterpret_cast<unsigned long long *>(out), z | (m << 32));      // out is 8-byte aligned
+        if (m) atomicAdd(reinterpret_cast<unsigned long long *>(out + 2 * which), z | (m << 32));    // 8-byte aligned
     }
 }
 
@@ -279,19 +290,24 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
                               hipStream_t s, unsigned dense_thr)
 {
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(5), 0, s, counters, dense_thr);
+    SampleArgs a;
     const float *t[2] = {x, dy};
     const size_t n[2] = {nx, ny};
+    size_t most = 1;
     for (int i = 0; i < 2; ++i) {
+        a.t[i] = t[i]; a.n[i] = t[i] ? n[i] : 0; a.stride[i] = 1; a.sampled[i] = 0;
         if (!t[i]) continue;
         const size_t blocks = (n[i] + 1023) / 1024;
         // every 8th block; fewer for huge tensors (the 32-bit counters hold at most 2^30 sampled
         // elements), all of them for small ones
         size_t stride = blocks < 64 ? 1 : 8;
         while ((blocks + stride - 1) / stride > (1u << 20)) stride *= 2;
-        const size_t sampled = (blocks + stride - 1) / stride;
-        hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(sampled < 256 ? sampled : 256)), dim3(256), 0, s, t[i],
-                           n[i], (unsigned)stride, sampled, counters + 2 * i);
+        a.stride[i] = (unsigned)stride;
+        a.sampled[i] = (blocks + stride - 1) / stride;
+        if (a.sampled[i] > most) most = a.sampled[i];
     }
+    hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(most < 256 ? most : 256), dy ? 2 : 1), dim3(256), 0, s, a,
+                       counters);
     return hipGetLastError();
 }
 
