@@ -543,28 +543,34 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
 // order: a fixed tree, so the result does not depend on timing.  Layers with few filter elements
 // and many splits (1x1, 64 x 64) would otherwise leave the sum to a handful of threads.
 // dw may be the first partial itself (every element is read by the thread that later writes it).
+// The grid is capped and workgroups stride over the outputs: a launch whose form was not selected
+// (st_conv_bww_auto) then costs a few hundred workgroup dispatches instead of up to ten thousand.
 __global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, float4 *dw, size_t n4, int splits,
                                                           const unsigned *sel, int want)
 {
     if (deselected(sel, want)) return;
     __shared__ float4 red[16][64];
     const int o = threadIdx.x % 64, sl = threadIdx.x / 64;
-    const size_t i = (size_t)blockIdx.x * 64 + o;
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n4)
-        for (int p = sl; p < splits; p += 16) {
-            const float4 v = part[(size_t)p * n4 + i];
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    const size_t nblk = (n4 + 63) / 64;
+    for (size_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {       // uniform trip count per workgroup
+        const size_t i = blk * 64 + o;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < n4)
+            for (int p = sl; p < splits; p += 16) {
+                const float4 v = part[(size_t)p * n4 + i];
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+        red[sl][o] = s;
+        __syncthreads();
+        if (sl == 0 && i < n4) {
+            const int lanes = splits < 16 ? splits : 16;
+            for (int q = 1; q < lanes; ++q) {
+                const float4 v = red[q][o];
+                s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+            }
+            dw[i] = s;
         }
-    red[sl][o] = s;
-    __syncthreads();
-    if (sl == 0 && i < n4) {
-        const int lanes = splits < 16 ? splits : 16;
-        for (int q = 1; q < lanes; ++q) {
-            const float4 v = red[q][o];
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-        }
-        dw[i] = s;
+        __syncthreads();                                    // red is rewritten by the next round
     }
 }
 
@@ -576,22 +582,27 @@ __global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__
                                                                  int R, const unsigned *sel)
 {
     if (deselected(sel, 1)) return;
-    // one workgroup per 16x16 block (k block, c block, tap) of dw: the source block [ki][ci] is read
-    // row by row (coalesced), then written transposed through LDS
+    // a workgroup per 16x16 block (k block, c block, tap) of dw at a time: the source block [ki][ci] is
+    // read row by row (coalesced), then written transposed through LDS
     __shared__ float tile[kBlk][kBlk + 1];
-    int t = blockIdx.x;
-    const int u = t % R; t /= R;
-    const int v = t % S; t /= S;
-    const int cb = t % (C / kBlk);
-    const int kb = t / (C / kBlk);
+    const int nblk = (K / kBlk) * (C / kBlk) * S * R;
     const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
-    const size_t src = ((((size_t)cb * (K / kBlk) + kb) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) +
-                       a * kBlk + b;                                       // element [ki = a][ci = b]
-    tile[a][b] = part[src];
-    __syncthreads();
-    dw[((((size_t)kb * (C / kBlk) + cb) * S + v) * R + u) * (kBlk * kBlk) + a * kBlk + b] = tile[b][a];   // [ci = a][ki = b]
+    for (int blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        int t = blk;
+        const int u = t % R; t /= R;
+        const int v = t % S; t /= S;
+        const int cb = t % (C / kBlk);
+        const int kb = t / (C / kBlk);
+        const size_t src = ((((size_t)cb * (K / kBlk) + kb) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) +
+                           a * kBlk + b;                                   // element [ki = a][ci = b]
+        tile[a][b] = part[src];
+        __syncthreads();
+        dw[((((size_t)kb * (C / kBlk) + cb) * S + v) * R + u) * (kBlk * kBlk) + a * kBlk + b] = tile[b][a];   // [ci = a][ki = b]
+        __syncthreads();
+    }
 }
 
+constexpr size_t kReduceGrid = 512;          // workgroups of 1024 threads: two per compute unit
 constexpr int kSparseTH = 8, kSparseTW = 8;
 constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
 // stride-2 layers: 4x8 tiles keep the strided halo of the other operand (9x17 pixels x 64 channels) in LDS
@@ -654,7 +665,8 @@ hipError_t reduce(const st_conv_desc &d, const BwwArgs &A, const float *part, fl
 {
     if (A.splits == 1) return hipSuccess;               // the kernel wrote dw itself
     const size_t n4 = (size_t)d.K * d.C * d.S * d.R / 4;
-    hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((n4 + 63) / 64)), dim3(1024), 0, s,
+    const size_t nblk = (n4 + 63) / 64;
+    hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)(nblk < kReduceGrid ? nblk : kReduceGrid)), dim3(1024), 0, s,
                        reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(dw), n4, A.splits, A.sel,
                        A.want);
     return hipGetLastError();
@@ -667,14 +679,16 @@ hipError_t reduce_swapped(const st_conv_desc &d, int splits, float *part, float 
 {
     const size_t total = (size_t)d.K * d.C * d.S * d.R;
     if (splits > 1) {
-        hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)((total / 4 + 63) / 64)), dim3(1024), 0, s,
+        const size_t nblk = (total / 4 + 63) / 64;
+        hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)(nblk < kReduceGrid ? nblk : kReduceGrid)), dim3(1024), 0, s,
                            reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(part), total / 4, splits,
                            sel, 1);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(total / 256)), dim3(256), 0, s, part, dw, d.K, d.C,
-                       d.S, d.R, sel);
+    const size_t tblk = total / 256;
+    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(tblk < 4 * kReduceGrid ? tblk : 4 * kReduceGrid)), dim3(256), 0,
+                       s, part, dw, d.K, d.C, d.S, d.R, sel);
     return hipGetLastError();
 }
 
@@ -859,12 +873,12 @@ hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *
 
 // Measured on the layer shapes of the paper's Table 1: the 3x3 zero-skipping forms pass the dense one at 30-35 % zeros;
 // a 1x1 layer saves at most K/64 (or C/64) multiply-adds per zero and stays behind the matrix cores up
-// to about 90 % zeros.  (Stride-2 layers never get here: their dy-testing form beats the dense one
+// to about 90 % zeros, and sampling two tensors costs a quarter of such a short launch: never (1001).  (Stride-2 layers never get here: their dy-testing form beats the dense one
 // even without zeros.)
 unsigned bww_sparse_threshold(const st_conv_desc &d)
 {
     if (!bww_fast_supported(d)) return 0;           // generic kernels: the test only ever removes work
-    return d.R == 1 ? 900 : 350;
+    return d.R == 1 ? 1001 : 350;
 }
 
 }  // namespace st

@@ -273,6 +273,7 @@ st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, f
     // the dense form takes part in the choice where tiled kernels exist for all three
     const bool tiled = st::bww_fast_supported(*d) && st::bww_dy_fast_supported(*d);
     const unsigned dense_thr = tiled ? st::bww_sparse_threshold(*d) : 0;
+    if (dense_thr > 1000) return dev(st::launch_bww_dense(*d, x, dy, dw, part, s));    // never zero-skipping: unsampled
     if (st::launch_zero_sample(x, nx, dy, ny, sel, s, dense_thr) != hipSuccess) return ST_ERR_DEVICE;
     hipError_t e = st::bww_fast_supported(*d) ? st::launch_bww_sparse(*d, x, dy, dw, part, s, sel)
                                               : st::launch_generic_bww(*d, x, dy, dw, true, s, sel);

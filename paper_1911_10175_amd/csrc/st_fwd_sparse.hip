@@ -402,7 +402,7 @@ unsigned fwd_sparse_threshold(const Geom &g)
     if (!fwd_sparse_supported(g)) return 0;         // generic kernels: the test only ever removes work
     if (g.R == 1) return g.Ko % 256 == 0 ? 900 : 1001;
     if (g.sw == 2) return 800;
-    if (g.uw == 2) return 500;
+    if (g.uw == 2) return 450;
     // launches with so few tasks that the reduction is split 16 ways (launch_fwd_sparse): the dense
     // form has no such split and leaves most of the chip idle; the zero-skipping form wins at any
     // sparsity (1.2-1.6x at 0 % zeros on 7x7 and 14x14 layers)
