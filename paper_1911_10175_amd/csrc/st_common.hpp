@@ -96,7 +96,7 @@ hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float
                               bool sparse, hipStream_t s, const unsigned *sel = nullptr);
 hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                                  hipStream_t s, const unsigned *sel = nullptr);
-// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of one block in eight; dy may be null);
+// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of about 1024 evenly spaced blocks of 1024 elements; dy may be null);
 // counters[4] = dense_thr, the per-mille zero fraction below which st_conv_bww_auto runs its dense form
 hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
                               hipStream_t s, unsigned dense_thr = 0);

@@ -298,10 +298,10 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
         a.t[i] = t[i]; a.n[i] = t[i] ? n[i] : 0; a.stride[i] = 1; a.sampled[i] = 0;
         if (!t[i]) continue;
         const size_t blocks = (n[i] + 1023) / 1024;
-        // every 8th block; fewer for huge tensors (the 32-bit counters hold at most 2^30 sampled
-        // elements), all of them for small ones
-        size_t stride = blocks < 64 ? 1 : 8;
-        while ((blocks + stride - 1) / stride > (1u << 20)) stride *= 2;
+        // about 1024 blocks spread evenly over the tensor (all of them when there are fewer): 10^6
+        // elements fix a zero fraction to a fraction of a per cent, and the pass stays a few
+        // microseconds whatever the tensor size
+        const size_t stride = (blocks + 1023) / 1024;
         a.stride[i] = (unsigned)stride;
         a.sampled[i] = (blocks + stride - 1) / stride;
         if (a.sampled[i] > most) most = a.sampled[i];

@@ -207,11 +207,11 @@ def test_stride2_degenerate_sparsity():
 
 
 def sampled_zero_counts(packed: np.ndarray):
-    """The library's sampling recipe, restated: blocks of 1024 consecutive floats, every 8th block
-    (all blocks when there are fewer than 64)."""
+    """The library's sampling recipe, restated: blocks of 1024 consecutive floats, every stride-th
+    block with stride = ceil(blocks / 1024) (all blocks when there are at most 1024)."""
     flat = packed.reshape(-1)
     blocks = (flat.size + 1023) // 1024
-    stride = 1 if blocks < 64 else 8
+    stride = (blocks + 1023) // 1024
     zeros = seen = 0
     for b in range(0, blocks, stride):
         chunk = flat[b * 1024:(b + 1) * 1024]
