@@ -157,8 +157,7 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
  * fraction reaches the break-even point measured for the geometry (40 % for 3x3 layers with K a
  * multiple of 128, 62 % for narrower ones, 80 % / 45 % for FWD / BWI of stride-2 3x3 layers, 90 %
  * for 1x1 layers with K a multiple of 256 and never for other 1x1 layers; always for geometries
- * only the generic kernels cover, and for unit-stride 3x3 launches of at most 256 tile tasks with C a
- * multiple of 256, which only the zero-skipping form can spread over the chip).  Where the answer is
+ * only the generic kernels cover).  Where the answer is
  * "always" or "never" the call goes straight to that form, without sampling.  The sampled path costs
  * about 15 us over the direct call; a caller that tracks sparsity itself can compare it with
  * st_conv_sparse_threshold and call the form directly.  Same tensors and layouts as st_conv_fwd /

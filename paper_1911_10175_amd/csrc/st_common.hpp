@@ -116,6 +116,9 @@ bool fwd_dense_supported(const Geom &g);
 // the dense kernel reads filters from a reformatted copy (fwd_dense_filter_bytes) written by
 // launch_reformat_filters; transpose selects the BWI form (channel roles swapped, taps reversed)
 size_t fwd_dense_filter_bytes(const Geom &g);
+// whole workspace of the dense form: the filter copy, then the partial outputs of launches whose
+// reduction is split over workgroups (few pixel tiles)
+size_t fwd_dense_workspace_bytes(const Geom &g);
 hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w, float *wd, hipStream_t s);
 hipError_t launch_fwd_dense(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s);
 // 1x1 layers with small filter matrices: whole filter in LDS, read from the library layout (no copy

@@ -73,13 +73,13 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
     switch (pass) {
     case ST_PASS_FWD: {
         const Geom g = fwd_geom(d, o);
-        if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
+        if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_workspace_bytes(g) : 0;
         return st::fwd_sparse_supported(g) ? st::fwd_sparse_filter_bytes(g) : 0;
     }
     case ST_PASS_BWI: {
         Geom g;
         if (!bwi_as_fwd(d, o, &g)) return 0;
-        if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_filter_bytes(g) : 0;
+        if (dense) return st::fwd_dense_supported(g) ? st::fwd_dense_workspace_bytes(g) : 0;
         return st::fwd_sparse_supported(g) ? st::fwd_sparse_filter_bytes(g) : 0;
     }
     case ST_PASS_BWW:
@@ -119,7 +119,7 @@ st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *
     const Geom g = fwd_geom(*d, o);
     if (dense) {
         if (!st::fwd_dense_supported(g)) return dev(st::launch_generic_fwd(*d, x, w, y, false, s));
-        if (!ws_ok(ws, ws_bytes, st::fwd_dense_filter_bytes(g))) return ST_ERR_WORKSPACE;
+        if (!ws_ok(ws, ws_bytes, st::fwd_dense_workspace_bytes(g))) return ST_ERR_WORKSPACE;
         if (st::pw_dense_direct_supported(g)) return dev(st::launch_pw_dense_direct(g, false, x, w, y, s));
         float *wd = static_cast<float *>(ws);
         if (st::launch_reformat_filters(g, false, w, wd, s) != hipSuccess) return ST_ERR_DEVICE;
@@ -146,7 +146,7 @@ st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float 
     if (!fast) return dev(st::launch_generic_bwi(*d, dy, w, dx, !dense, s));
     float *wt = static_cast<float *>(ws);
     if (dense) {
-        if (!ws_ok(ws, ws_bytes, st::fwd_dense_filter_bytes(g))) return ST_ERR_WORKSPACE;
+        if (!ws_ok(ws, ws_bytes, st::fwd_dense_workspace_bytes(g))) return ST_ERR_WORKSPACE;
         if (st::pw_dense_direct_supported(g)) return dev(st::launch_pw_dense_direct(g, true, dy, w, dx, s));
         if (st::launch_reformat_filters(g, true, w, wt, s) != hipSuccess) return ST_ERR_DEVICE;
         return dev(st::launch_fwd_dense(g, dy, wt, dx, s));

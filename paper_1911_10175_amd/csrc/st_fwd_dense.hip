@@ -64,7 +64,8 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
     Geom g, const float *__restrict__ in,
                                                            const float *__restrict__ wd,
                                                            float *__restrict__ out, int tiles_w,
-                                                           int tiles_h, int kgroups, int total_tiles)
+                                                           int tiles_h, int kgroups, int total_tiles,
+                                                           int csplit, size_t part_stride)
 {
     using Cfg = FwdDenseCfg<R, S, TWD, MODE, PI, PJ>;
     if (form_deselected(g.sel, g.want, g.thr)) return;
@@ -86,6 +87,10 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
     const int oh0 = th * TH, ow0 = tw * TW;         // MODE 2: in units of the parity class's own grid
     const int ih0 = MODE == 2 ? oh0 : oh0 * PSTEP - g.ph, iw0 = MODE == 2 ? ow0 : ow0 * PSTEP - g.pw;
     const int CiB = g.Ci / kBlk, KoB = g.Ko / kBlk;
+    // channel split (launches with few tiles): workgroup row blockIdx.y reduces its share of the
+    // channel blocks into its own partial output, which sum_partials_kernel adds up afterwards
+    const int cb0 = blockIdx.y * (CiB / csplit), cb1 = cb0 + CiB / csplit;        // CiB % csplit == 0
+    out += blockIdx.y * part_stride;
     const int kb32 = kg * KQ + kqi;                 // this wavefront's column block
     const bool k_ok = kb32 * 32 < g.Ko;
     const bool active = tile_ok && k_ok;
@@ -141,20 +146,20 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
     constexpr int kWaitOlder = vmcnt_imm(2);          // all but the 2 newest loads
     float bcur[8], bnxt[8];
     float4 hreg[NLD];
-    load_halo(0, hreg);
+    load_halo(cb0, hreg);
     store_halo(lds_all[0][tqi], hreg);
-    load_b(Cfg::ftap(0), bcur);
+    load_b(cb0 * TAPS + Cfg::ftap(0), bcur);
     __syncthreads();
 
-    for (int cb = 0; cb < CiB; ++cb) {
-        const float *lds = lds_all[cb & 1][tqi];
+    for (int cb = cb0; cb < cb1; ++cb) {
+        const float *lds = lds_all[(cb - cb0) & 1][tqi];
 #pragma unroll
         for (int tp = 0; tp < NT; ++tp) {
             {
                 const int v = Cfg::dv(tp), u = Cfg::du(tp);
                 // next step's filters fly during this step's MFMAs (the last step re-reads its own)
                 const int nstep = tp + 1 < NT ? cb * TAPS + Cfg::ftap(tp + 1 < NT ? tp + 1 : 0)
-                                              : min(cb + 1, CiB - 1) * TAPS + Cfg::ftap(0);
+                                              : min(cb + 1, cb1 - 1) * TAPS + Cfg::ftap(0);
                 load_b(nstep, bnxt);
                 __builtin_amdgcn_sched_barrier(0);              // keep these loads ahead of the MFMAs below
                 float a[2][8];
@@ -170,7 +175,7 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
                 __builtin_amdgcn_sched_barrier(0);
                 // The next block's halo is requested here, after the wait, so that the first wait
                 // that covers these loads is the one of the next tap: they land during the MFMAs.
-                if (tp == 0 && cb + 1 < CiB) {
+                if (tp == 0 && cb + 1 < cb1) {
                     load_halo(cb + 1, hreg);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -185,7 +190,7 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
                 for (int j = 0; j < 8; ++j) bcur[j] = bnxt[j];
             }
         }
-        if (cb + 1 < CiB) store_halo(lds_all[(cb + 1) & 1][tqi], hreg);
+        if (cb + 1 < cb1) store_halo(lds_all[(cb + 1 - cb0) & 1][tqi], hreg);
         __syncthreads();
     }
 
@@ -243,6 +248,51 @@ __global__ __launch_bounds__(256) void reformat_filters_kernel(int Ko, int Ci, i
     wd[i] = val;
 }
 
+// out = part[0] + part[1] + ... (fixed order), float4 at a time, on a capped grid
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float4 *__restrict__ part, float4 *__restrict__ out,
+                                                           size_t n4, int splits, const unsigned *sel, unsigned thr)
+{
+    if (form_deselected(sel, 1, thr)) return;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+        float4 a = part[i];
+        for (int p = 1; p < splits; ++p) {
+            const float4 v = part[(size_t)p * n4 + i];
+            a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        }
+        out[i] = a;
+    }
+}
+
+// Tile width and column blocks per workgroup of a unit-stride launch (the choice launch_rs and
+// launch_kq make), and the number of workgroups that results
+void dense_tiling(const Geom &g, int *twd, int *kq, long long *blocks)
+{
+    // tile width that divides the row length, if any: 8 -> 8x8, 28 -> 2x28, 14 -> 4x14
+    *twd = (g.Wo % 8 != 0 && g.Wo % 28 == 0 && g.Ho % 2 == 0) ? 28
+         : (g.Wo % 8 != 0 && g.Wo % 14 == 0 && g.Ho % 4 <= g.Ho % 8) ? 14 : 8;
+    *kq = g.Ko > 64 ? 4 : (g.Ko > 32 ? 2 : 1);
+    const long long tiles = (long long)ceil_div(g.Wo, *twd) * ceil_div(g.Ho, 64 / *twd) * g.N;
+    const int tq = 4 / *kq;
+    *blocks = (tiles + tq - 1) / tq * ceil_div(g.Ko, 32 * *kq);
+}
+
+// Channel split of the unit-stride 3x3 launches that would leave most of the chip idle (7x7 and 14x14
+// layers: a workgroup per pixel tile and 128 output channels gives 128 workgroups for 512 -> 512 @7,
+// N = 32, each walking all 512 input channels): 2, 4 or 8 shares, enough for about two workgroups per
+// compute unit.  Depends on the geometry only, so that the workspace query and the launch agree.
+int dense_channel_split(const Geom &g)
+{
+    if (g.R != 3 || g.S != 3 || g.sw != 1 || g.uw != 1) return 1;
+    int twd, kq;
+    long long blocks;
+    dense_tiling(g, &twd, &kq, &blocks);
+    if (blocks >= 384) return 1;
+    const int CiB = g.Ci / kBlk;
+    int cs = 1;
+    while (cs < 8 && blocks * cs < 512 && CiB % (cs * 2) == 0 && CiB / (cs * 2) >= 2) cs *= 2;
+    return cs;
+}
+
 template <int R, int S, int KQ, int TWD, int MODE = 0, int PI = 0, int PJ = 0>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
@@ -256,8 +306,17 @@ hipError_t launch_cfg(const Geom &g, const float *in, const float *wd, float *ou
     const int kgroups = ceil_div(g.Ko, 32 * KQ);
     const long long blocks = (total_tiles + TQ - 1) / TQ * kgroups;
     if (total_tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ, TWD, MODE, PI, PJ>), dim3((unsigned)blocks), dim3(256), 0, s, g, in, wd, out,
-                       tiles_w, tiles_h, kgroups, (int)total_tiles);
+    const int cs = MODE == 0 ? dense_channel_split(g) : 1;
+    const size_t n_out = (size_t)g.N * g.Ko * g.Ho * g.Wo;
+    // partial outputs sit behind the filter copy in the workspace
+    float *part = cs > 1 ? const_cast<float *>(wd) + (fwd_dense_filter_bytes(g) + 255) / 256 * 256 / sizeof(float) : out;
+    hipLaunchKernelGGL((fwd_dense_kernel<R, S, KQ, TWD, MODE, PI, PJ>), dim3((unsigned)blocks, cs), dim3(256), 0, s, g, in, wd,
+                       part, tiles_w, tiles_h, kgroups, (int)total_tiles, cs, n_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || cs == 1) return e;
+    const size_t n4 = n_out / 4;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)(n4 / 256 + 1 < 1024 ? n4 / 256 + 1 : 1024)), dim3(256), 0, s,
+                       reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(out), n4, cs, g.sel, g.thr);
     return hipGetLastError();
 }
 
@@ -303,9 +362,11 @@ hipError_t launch_s2_bwi(const Geom &g, const float *in, const float *wd, float 
 template <int R, int S>
 hipError_t launch_rs(const Geom &g, const float *in, const float *wd, float *out, hipStream_t s)
 {
-    // tile width that divides the row length, if any: 8 -> 8x8, 28 -> 2x28, 14 -> 4x14
-    if (g.Wo % 8 != 0 && g.Wo % 28 == 0 && g.Ho % 2 == 0) return launch_kq<R, S, 28>(g, in, wd, out, s);
-    if (g.Wo % 8 != 0 && g.Wo % 14 == 0 && g.Ho % 4 <= g.Ho % 8) return launch_kq<R, S, 14>(g, in, wd, out, s);
+    int twd, kq;
+    long long blocks;
+    dense_tiling(g, &twd, &kq, &blocks);
+    if (twd == 28) return launch_kq<R, S, 28>(g, in, wd, out, s);
+    if (twd == 14) return launch_kq<R, S, 14>(g, in, wd, out, s);
     return launch_kq<R, S, 8>(g, in, wd, out, s);
 }
 
@@ -326,6 +387,15 @@ size_t fwd_dense_filter_bytes(const Geom &g)
 {
     // output channels padded to a multiple of 128 so that every column block a workgroup touches exists
     return (size_t)ceil_div(g.Ko, 128) * 128 * g.Ci * g.S * g.R * sizeof(float);
+}
+
+size_t fwd_dense_workspace_bytes(const Geom &g)
+{
+    // filter copy, then the partial outputs of a channel-split launch
+    const size_t n = fwd_dense_filter_bytes(g);
+    const int cs = dense_channel_split(g);
+    if (cs == 1) return n;
+    return (n + 255) / 256 * 256 + (size_t)cs * g.N * g.Ko * g.Ho * g.Wo * sizeof(float);
 }
 
 hipError_t launch_reformat_filters(const Geom &g, bool transpose, const float *w, float *wd, hipStream_t s)

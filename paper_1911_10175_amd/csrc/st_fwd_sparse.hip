@@ -403,13 +403,7 @@ unsigned fwd_sparse_threshold(const Geom &g)
     if (g.R == 1) return g.Ko % 256 == 0 ? 900 : 1001;
     if (g.sw == 2) return 800;
     if (g.uw == 2) return 450;
-    // launches with so few tasks that the reduction is split 16 ways (launch_fwd_sparse): the dense
-    // form has no such split and leaves most of the chip idle; the zero-skipping form wins at any
-    // sparsity (1.2-1.6x at 0 % zeros on 7x7 and 14x14 layers)
-    const bool wide = g.Ko % 128 == 0, seven = g.Wo % 8 != 0 && g.Wo % 7 == 0;
-    const long long tasks = (long long)ceil_div(g.Wo, seven ? 7 : 8) * ceil_div(g.Ho, wide ? 4 : 8) *
-                            ceil_div(g.Ko, wide ? 128 : 64) * g.N;
-    if (tasks <= 256 && (g.Ci / kBlk) % 16 == 0) return 0;
+    const bool wide = g.Ko % 128 == 0;
     return wide ? 400 : 620;
 }
 

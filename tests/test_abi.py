@@ -130,9 +130,11 @@ def test_sparse_threshold_policy():
     assert st.st_conv_sparse_threshold(s2, F) == 800 and st.st_conv_sparse_threshold(s2, B) == 450
     pw = st.ConvDesc(8, 64, 256, 56, 56, 1, 1)
     assert st.st_conv_sparse_threshold(pw, F) == 900 and st.st_conv_sparse_threshold(pw, B) == 1001
-    # so few tasks that the reduction is split 16 ways: the dense form cannot fill the chip either
+    # launches with few tasks split their reduction in both forms: same break-even as the large ones
     tiny = st.ConvDesc(32, 512, 512, 7, 7, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(tiny, F) == 0 and st.st_conv_sparse_threshold(tiny, B) == 0
+    assert st.st_conv_sparse_threshold(tiny, F) == 400 and st.st_conv_sparse_threshold(tiny, B) == 400
+    # the dense form's workspace then also holds the partial outputs of its channel split
+    assert st.st_conv_workspace_bytes(tiny, F, True) == 512 * 512 * 9 * 4 + 4 * 32 * 512 * 49 * 4      # 4 shares
     # only generic kernels: the test can only remove work
     assert st.st_conv_sparse_threshold(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), F) == 0
     assert st.st_conv_sparse_threshold(st.ConvDesc(0, 16, 16, 9, 9, 3, 3), F) == -1

@@ -275,16 +275,18 @@ def test_fwd_bwi_auto_pick_the_form_by_sparsity(p, form):
     assert np.array_equal(got, L.bwi(form))
 
 
-def test_fwd_bwi_auto_small_launch_always_zero_skipping():
-    """A unit-stride 3x3 launch of at most 256 tasks whose reduction splits 16 ways: only the
-    zero-skipping form spreads over the chip, so it is taken even at 10 % zeros."""
+def test_fwd_bwi_auto_small_launch():
+    """A launch of few tasks (both forms split their reduction over wavefronts / workgroups): the
+    usual break-even applies, and both forms agree with the oracle."""
     g = Geom(1, 256, 256, 7, 7, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(desc_of(g), st.ST_PASS_FWD) == 0
-    x, w, dy = synth(g, 0.1, 0.1, seed=63)
-    L = DeviceLayer(g, x, w, dy)
-    assert not np.array_equal(L.fwd(False), L.fwd(True)), "forms indistinguishable: test is void"
-    assert np.array_equal(L.fwd("auto"), L.fwd(False))
-    assert np.array_equal(L.bwi("auto"), L.bwi(False))
+    assert st.st_conv_sparse_threshold(desc_of(g), st.ST_PASS_FWD) == 400
+    for p, form in ((0.1, True), (0.9, False)):
+        x, w, dy = synth(g, p, p, seed=63)
+        L = DeviceLayer(g, x, w, dy)
+        assert not np.array_equal(L.fwd(False), L.fwd(True)), "forms indistinguishable: test is void"
+        assert np.array_equal(L.fwd("auto"), L.fwd(form))
+        assert np.array_equal(L.bwi("auto"), L.bwi(form))
+        check_all_passes_full(g, x, w, dy, f"small launch p={p}", passes=("fwd", "bwi"))
 
 
 def test_fwd_auto_1x1_never_takes_the_narrow_sparse_form():
