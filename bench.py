@@ -27,8 +27,8 @@ PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
 
 # HBM traffic per launch of the dominant kernel (fwd_sparse_kernel on this workload) from two
 # rocprofv3 --pmc runs, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 (factors from a 256 MiB copy of known
-# size): 47569.5 KiB * 2 + 50176.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = int((47569.5 * 2.0 + 50176.0) * 1024)
+# size): 47598.0 KiB * 2 + 50176.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
+MEASURED_TRAFFIC_BYTES = int((47598.0 * 2.0 + 50176.0) * 1024)
 
 
 def write_config_table(path, st, stgen, torch, dev, stream):
