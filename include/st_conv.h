@@ -138,7 +138,7 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
  * strictly larger zero fraction.  Same tensors, same result, no host synchronisation; the cost is
  * the sampling pass (at most 4 MB of x and of dy are read once more) and the empty launches.  Where tiled
  * kernels exist, the dense form (st_conv_bww_dense) is the third candidate: it runs when even the
- * sparser operand has fewer zeros than the measured break-even, 30 % for 3x3 layers (Sec. 5.3
+ * sparser operand has fewer zeros than the measured break-even, 25 % for 3x3 layers (Sec. 5.3
  * combines the kernels with dense ones layer by layer); 1x1 layers, where a zero saves too few
  * multiply-adds to beat the matrix cores below about 90 % zeros, go straight to it, unsampled.  Stride-2 3x3
  * layers are the exception: there dy is always tested, without sampling (x has four times the
@@ -154,7 +154,7 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
  * profiled sparsity; here a first kernel counts the zeros in a sample of the tested operand (x for
  * FWD, dy for BWI; about 1024 evenly spaced blocks of 1024 elements), then both forms are enqueued and the one
  * the count does not select returns at once.  The zero-skipping form runs when the sampled zero
- * fraction reaches the break-even point measured for the geometry (30 % for 3x3 layers with K a
+ * fraction reaches the break-even point measured for the geometry (25 % for 3x3 layers with K a
  * multiple of 128, 62 % for narrower ones, 80 % / 45 % for FWD / BWI of stride-2 3x3 layers, 90 %
  * for 1x1 layers with K a multiple of 256 and never for other 1x1 layers; always for geometries
  * only the generic kernels cover).  Where the answer is

@@ -120,19 +120,19 @@ def test_sparse_threshold_policy():
     """Break-even points of the self-selecting FWD / BWI entry points (host-side query)."""
     F, B = st.ST_PASS_FWD, st.ST_PASS_BWI
     vgg = st.ConvDesc(16, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(vgg, F) == 300 and st.st_conv_sparse_threshold(vgg, B) == 300
+    assert st.st_conv_sparse_threshold(vgg, F) == 250 and st.st_conv_sparse_threshold(vgg, B) == 250
     narrow = st.ConvDesc(16, 64, 64, 56, 56, 3, 3, 1, 1, 1, 1)
     assert st.st_conv_sparse_threshold(narrow, F) == 620
     # FWD vectorises over K, BWI over C
     mixed = st.ConvDesc(16, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(mixed, F) == 300 and st.st_conv_sparse_threshold(mixed, B) == 620
+    assert st.st_conv_sparse_threshold(mixed, F) == 250 and st.st_conv_sparse_threshold(mixed, B) == 620
     s2 = st.ConvDesc(8, 128, 128, 56, 56, 3, 3, 2, 2, 1, 1)
     assert st.st_conv_sparse_threshold(s2, F) == 800 and st.st_conv_sparse_threshold(s2, B) == 450
     pw = st.ConvDesc(8, 64, 256, 56, 56, 1, 1)
     assert st.st_conv_sparse_threshold(pw, F) == 900 and st.st_conv_sparse_threshold(pw, B) == 1001
     # launches with few tasks split their reduction in both forms: same break-even as the large ones
     tiny = st.ConvDesc(32, 512, 512, 7, 7, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(tiny, F) == 300 and st.st_conv_sparse_threshold(tiny, B) == 300
+    assert st.st_conv_sparse_threshold(tiny, F) == 250 and st.st_conv_sparse_threshold(tiny, B) == 250
     # the dense form's workspace then also holds the partial outputs of its channel split
     assert st.st_conv_workspace_bytes(tiny, F, True) == 512 * 512 * 9 * 4 + 4 * 32 * 512 * 49 * 4      # 4 shares
     # only generic kernels: the test can only remove work
