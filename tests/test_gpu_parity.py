@@ -343,7 +343,7 @@ def random_geometries(count, seed):
     return out
 
 
-RANDOM_GEOMS = random_geometries(48, seed=2024)
+RANDOM_GEOMS = random_geometries(120, seed=2024)
 
 
 @pytest.mark.parametrize("i", range(len(RANDOM_GEOMS)))
@@ -354,6 +354,33 @@ def test_random_geometries_all_entry_points(i):
     if i % 4 == 0:
         x = stgen.dead_channels(x, 0.4, 900 + i)
     check_all_passes_full(g, x, w, dy, f"random#{i} {g}")
+
+
+def wide_geometries(count, seed):
+    """Seeded geometries of the tiled paths with up to 640 channels and up to 30 x 30 pixels: every
+    channel split, several 64-channel groups, ragged tiles."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 3, 3]))
+        s = int(rng.choice([1, 1, 1, 2])) if R == 3 else 1
+        H, W = int(rng.integers(5, 31)), int(rng.integers(5, 31))
+        C, K = 16 * int(rng.integers(1, 41)), 16 * int(rng.integers(1, 41))
+        if C * K * R * R * H * W * 2 > 4e9:
+            continue
+        out.append(Geom(int(rng.integers(1, 4)), C, K, H, W, R, R, s, s, (R - 1) // 2, (R - 1) // 2))
+    return out
+
+
+WIDE_GEOMS = wide_geometries(40, seed=6)
+
+
+@pytest.mark.parametrize("i", range(len(WIDE_GEOMS)))
+def test_wide_geometries_all_entry_points(i):
+    g = WIDE_GEOMS[i]
+    px, pdy = [(0.5, 0.6), (0.8, 0.2), (0.3, 0.3)][i % 3]
+    x, w, dy = synth(g, px, pdy, seed=5000 + i)
+    check_all_passes_full(g, x, w, dy, f"wide#{i} {g}")
 
 
 def test_config3_resnet3_2_full():
