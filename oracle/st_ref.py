@@ -245,11 +245,18 @@ def rel_err(got, ref, ref_abs):
 
     Returns (max relative error over elements with a non-zero scale,
              number of elements whose scale is 0 but whose value is not).
+    A non-finite element of got counts as an infinite error (scale > 0) or as a bad zero (scale 0).
+    Pinned by tests/test_oracle_pins.py::test_rel_err_* (hand-computed cases, planted deviations).
     """
     got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    ref_abs = np.asarray(ref_abs, dtype=np.float64)
+    if got.shape != ref.shape or ref.shape != ref_abs.shape:
+        raise ValueError(f"shape mismatch: got {got.shape}, ref {ref.shape}, scale {ref_abs.shape}")
     nz = ref_abs > 0
     err = 0.0
     if nz.any():
-        err = float(np.max(np.abs(got[nz] - ref[nz]) / ref_abs[nz]))
-    bad_zero = int(np.count_nonzero(got[~nz] != 0.0))
+        e = np.abs(got[nz] - ref[nz]) / ref_abs[nz]
+        err = float("inf") if not np.isfinite(e).all() else float(np.max(e))
+    bad_zero = int(np.count_nonzero(~(got[~nz] == 0.0)))
     return err, bad_zero

@@ -16,9 +16,10 @@
  * products whose tested factor compares equal to zero, so it reaches exactly
  * the dense result; the oracle proper is therefore the plain definition
  * ("gather" form, one output at a time).  The paper's input-stationary
- * "scatter" forms with the zero test (Alg. 1, its BWI twin, Alg. 4) are also
- * written out here, in the paper's loop order, so that a test can check that
- * they agree with the definition and count what they skip.
+ * forms with the zero test (Alg. 1, its BWI twin, Alg. 4: the tested operand is
+ * visited element by element and a zero is dropped with all its products) are
+ * also written out here, so that a test can check that they agree with the
+ * definition and count what they skip.
  *
  * Symbols follow the paper's Table 1: N minibatch, C input channels, K output
  * channels, H x W input size, R filter WIDTH (pairs with W, iterator u),
@@ -318,18 +319,60 @@ int st_ref_conv_bww_at(const int32_t *dims, const float *x, const float *dy,
     return 0;
 }
 
-/* ============ the paper's input-stationary forms with the zero test ====== */
-/* The test is the IEEE comparison "value != 0": +0 and -0 are skipped,
- * denormals are not (Alg. 3 builds its mask with a vector compare against 0).
- * Serial on purpose: these follow the paper's naive algorithms, whose updates
- * to one output come from many inputs.  *n_skipped (optional) receives the
- * number of tested elements that were skipped. */
+/* ============ the zero-skipping forms (tested operand stationary) ========= */
+/* Sec. 3.1 (Alg. 1) and Sec. 3.4 (Alg. 4) visit the tested operand element by
+ * element, drop an element that compares equal to zero together with all of
+ * its products, and add the products of every other element to the outputs
+ * they belong to.  The test is the IEEE comparison "value != 0": +0 and -0
+ * are dropped, denormals are not (Alg. 3 builds its mask with a vector compare
+ * against 0).  These routines are organised around the list of (tap, partner
+ * pixel) pairs of one tested pixel, which is all the geometry there is; the
+ * channel loop of the untested side is innermost.  Serial on purpose: updates
+ * to one output come from many tested elements.  *n_skipped (optional)
+ * receives the number of tested elements that were dropped. */
 
-/* Alg. 1 (naive sparse FWD), generalised to stride and padding: the input
- * element at (ih,iw) reaches, through tap (v,u), the output at
- * oh = (ih + pad_h - v)/P, ow = (iw + pad_w - u)/O when those divide evenly
- * and fall inside the output; with O = P = 1 and no padding this is the
- * paper's Y[x-u, y-v]. */
+typedef struct { int v, u, ph, pw; } ref_link;     /* tap (v,u) and the partner pixel (ph,pw) */
+
+/* Pairs of an INPUT pixel (ih,iw): output pixel (oh,ow) reads it through tap
+ * (v,u) iff oh*P - pad_h + v == ih and ow*O - pad_w + u == iw.  With unit
+ * strides and no padding this is the paper's Y[x-u, y-v].  Returns the count
+ * (at most S*R). */
+static int links_of_input_pixel(const ref_geom *g, int ih, int iw, ref_link *l)
+{
+    int n = 0;
+    for (int v = 0; v < g->S; ++v) {
+        int th = ih + g->pad_h - v;
+        if (th < 0 || th % g->P || th / g->P >= g->OH) continue;
+        for (int u = 0; u < g->R; ++u) {
+            int tw = iw + g->pad_w - u;
+            if (tw < 0 || tw % g->O || tw / g->O >= g->OW) continue;
+            l[n].v = v; l[n].u = u; l[n].ph = th / g->P; l[n].pw = tw / g->O;
+            ++n;
+        }
+    }
+    return n;
+}
+
+/* Pairs of an OUTPUT pixel (oh,ow): the input pixels its taps read. */
+static int links_of_output_pixel(const ref_geom *g, int oh, int ow, ref_link *l)
+{
+    int n = 0;
+    for (int v = 0; v < g->S; ++v) {
+        int ih = oh * g->P - g->pad_h + v;
+        if (ih < 0 || ih >= g->H) continue;
+        for (int u = 0; u < g->R; ++u) {
+            int iw = ow * g->O - g->pad_w + u;
+            if (iw < 0 || iw >= g->W) continue;
+            l[n].v = v; l[n].u = u; l[n].ph = ih; l[n].pw = iw;
+            ++n;
+        }
+    }
+    return n;
+}
+
+enum { REF_MAX_TAPS = 1024 };
+
+/* FWD with the zero test on x (Sec. 3.1, Alg. 1). */
 int st_ref_conv_fwd_scatter(const int32_t *dims, const float *x, const float *w,
                             double *y, int64_t *n_skipped)
 {
@@ -337,34 +380,28 @@ int st_ref_conv_fwd_scatter(const int32_t *dims, const float *x, const float *w,
     int rc = ref_geom_init(&g, dims);
     if (rc) return rc;
     if (!x || !w || !y) return -1;
-    size_t ny = (size_t)g.N * g.K * g.OH * g.OW;
-    memset(y, 0, ny * sizeof(double));
+    if ((int64_t)g.S * g.R > REF_MAX_TAPS) return -5;
+    ref_link l[REF_MAX_TAPS];
+    memset(y, 0, (size_t)g.N * g.K * g.OH * g.OW * sizeof(double));
     int64_t skipped = 0;
-    for (int n = 0; n < g.N; ++n)
-        for (int c = 0; c < g.C; ++c)
-            for (int ih = 0; ih < g.H; ++ih)
-                for (int iw = 0; iw < g.W; ++iw) {
-                    float d = x[X_AT(g, n, c, ih, iw)];
-                    if (!(d != 0.0f)) { ++skipped; continue; }
-                    for (int k = 0; k < g.K; ++k)
-                        for (int v = 0; v < g.S; ++v) {
-                            int th = ih + g.pad_h - v;
-                            if (th < 0 || th % g.P || th / g.P >= g.OH) continue;
-                            for (int u = 0; u < g.R; ++u) {
-                                int tw = iw + g.pad_w - u;
-                                if (tw < 0 || tw % g.O || tw / g.O >= g.OW) continue;
-                                y[Y_AT(g, n, k, th / g.P, tw / g.O)] +=
-                                    (double)d * (double)w[W_AT(g, k, c, v, u)];
-                            }
-                        }
-                }
+    const int64_t total = (int64_t)g.N * g.C * g.H * g.W;
+    for (int64_t e = 0; e < total; ++e) {           /* e = flat index into x[N][C][H][W] */
+        const float d = x[e];
+        if (!(d != 0.0f)) { ++skipped; continue; }
+        const int iw = (int)(e % g.W), ih = (int)(e / g.W % g.H);
+        const int c = (int)(e / ((int64_t)g.W * g.H) % g.C), n = (int)(e / ((int64_t)g.W * g.H * g.C));
+        const int nl = links_of_input_pixel(&g, ih, iw, l);
+        for (int i = 0; i < nl; ++i)
+            for (int k = 0; k < g.K; ++k)
+                y[Y_AT(g, n, k, l[i].ph, l[i].pw)] += (double)d * (double)w[W_AT(g, k, c, l[i].v, l[i].u)];
+    }
     if (n_skipped) *n_skipped = skipped;
     return 0;
 }
 
-/* BWI counterpart ("the sparse algorithm for BWI is similar to FWD",
- * Sec. 3.1): each non-zero dy element is spread over the inputs it was
- * computed from, with the filter indexed by its input channel. */
+/* BWI with the zero test on dy (Sec. 3.1 treats BWI like FWD): each non-zero
+ * dy element is spread over the input pixels it was computed from, the filter
+ * being indexed by the input channel. */
 int st_ref_conv_bwi_scatter(const int32_t *dims, const float *dy, const float *w,
                             double *dx, int64_t *n_skipped)
 {
@@ -372,34 +409,28 @@ int st_ref_conv_bwi_scatter(const int32_t *dims, const float *dy, const float *w
     int rc = ref_geom_init(&g, dims);
     if (rc) return rc;
     if (!dy || !w || !dx) return -1;
-    size_t nx = (size_t)g.N * g.C * g.H * g.W;
-    memset(dx, 0, nx * sizeof(double));
+    if ((int64_t)g.S * g.R > REF_MAX_TAPS) return -5;
+    ref_link l[REF_MAX_TAPS];
+    memset(dx, 0, (size_t)g.N * g.C * g.H * g.W * sizeof(double));
     int64_t skipped = 0;
-    for (int n = 0; n < g.N; ++n)
-        for (int k = 0; k < g.K; ++k)
-            for (int oh = 0; oh < g.OH; ++oh)
-                for (int ow = 0; ow < g.OW; ++ow) {
-                    float d = dy[Y_AT(g, n, k, oh, ow)];
-                    if (!(d != 0.0f)) { ++skipped; continue; }
-                    for (int c = 0; c < g.C; ++c)
-                        for (int v = 0; v < g.S; ++v) {
-                            int ih = oh * g.P - g.pad_h + v;
-                            if (ih < 0 || ih >= g.H) continue;
-                            for (int u = 0; u < g.R; ++u) {
-                                int iw = ow * g.O - g.pad_w + u;
-                                if (iw < 0 || iw >= g.W) continue;
-                                dx[X_AT(g, n, c, ih, iw)] +=
-                                    (double)d * (double)w[W_AT(g, k, c, v, u)];
-                            }
-                        }
-                }
+    const int64_t total = (int64_t)g.N * g.K * g.OH * g.OW;
+    for (int64_t e = 0; e < total; ++e) {           /* e = flat index into dy[N][K][OH][OW] */
+        const float d = dy[e];
+        if (!(d != 0.0f)) { ++skipped; continue; }
+        const int ow = (int)(e % g.OW), oh = (int)(e / g.OW % g.OH);
+        const int k = (int)(e / ((int64_t)g.OW * g.OH) % g.K), n = (int)(e / ((int64_t)g.OW * g.OH * g.K));
+        const int nl = links_of_output_pixel(&g, oh, ow, l);
+        for (int i = 0; i < nl; ++i)
+            for (int c = 0; c < g.C; ++c)
+                dx[X_AT(g, n, c, l[i].ph, l[i].pw)] += (double)d * (double)w[W_AT(g, k, c, l[i].v, l[i].u)];
+    }
     if (n_skipped) *n_skipped = skipped;
     return 0;
 }
 
-/* Alg. 4 (naive sparse BWW).  test_dy = 0 tests the input x as printed;
- * test_dy = 1 tests dy instead (the variant Sec. 3.4 mentions for layers
- * whose dy is the sparser operand). */
+/* BWW with the zero test on x (Sec. 3.4, Alg. 4; test_dy = 0) or on dy
+ * (test_dy = 1: the variant Sec. 3.4 mentions for layers whose dy is the
+ * sparser operand). */
 int st_ref_conv_bww_scatter(const int32_t *dims, const float *x, const float *dy,
                             int test_dy, double *dw, int64_t *n_skipped)
 {
@@ -407,47 +438,34 @@ int st_ref_conv_bww_scatter(const int32_t *dims, const float *x, const float *dy
     int rc = ref_geom_init(&g, dims);
     if (rc) return rc;
     if (!x || !dy || !dw) return -1;
-    size_t nw = (size_t)g.K * g.C * g.S * g.R;
-    memset(dw, 0, nw * sizeof(double));
+    if ((int64_t)g.S * g.R > REF_MAX_TAPS) return -5;
+    ref_link l[REF_MAX_TAPS];
+    memset(dw, 0, (size_t)g.K * g.C * g.S * g.R * sizeof(double));
     int64_t skipped = 0;
     if (!test_dy) {
-        for (int n = 0; n < g.N; ++n)
-            for (int c = 0; c < g.C; ++c)
-                for (int ih = 0; ih < g.H; ++ih)
-                    for (int iw = 0; iw < g.W; ++iw) {
-                        float d = x[X_AT(g, n, c, ih, iw)];
-                        if (!(d != 0.0f)) { ++skipped; continue; }
-                        for (int k = 0; k < g.K; ++k)
-                            for (int v = 0; v < g.S; ++v) {
-                                int th = ih + g.pad_h - v;
-                                if (th < 0 || th % g.P || th / g.P >= g.OH) continue;
-                                for (int u = 0; u < g.R; ++u) {
-                                    int tw = iw + g.pad_w - u;
-                                    if (tw < 0 || tw % g.O || tw / g.O >= g.OW) continue;
-                                    dw[W_AT(g, k, c, v, u)] +=
-                                        (double)d * (double)dy[Y_AT(g, n, k, th / g.P, tw / g.O)];
-                                }
-                            }
-                    }
+        const int64_t total = (int64_t)g.N * g.C * g.H * g.W;
+        for (int64_t e = 0; e < total; ++e) {
+            const float d = x[e];
+            if (!(d != 0.0f)) { ++skipped; continue; }
+            const int iw = (int)(e % g.W), ih = (int)(e / g.W % g.H);
+            const int c = (int)(e / ((int64_t)g.W * g.H) % g.C), n = (int)(e / ((int64_t)g.W * g.H * g.C));
+            const int nl = links_of_input_pixel(&g, ih, iw, l);
+            for (int i = 0; i < nl; ++i)
+                for (int k = 0; k < g.K; ++k)
+                    dw[W_AT(g, k, c, l[i].v, l[i].u)] += (double)d * (double)dy[Y_AT(g, n, k, l[i].ph, l[i].pw)];
+        }
     } else {
-        for (int n = 0; n < g.N; ++n)
-            for (int k = 0; k < g.K; ++k)
-                for (int oh = 0; oh < g.OH; ++oh)
-                    for (int ow = 0; ow < g.OW; ++ow) {
-                        float d = dy[Y_AT(g, n, k, oh, ow)];
-                        if (!(d != 0.0f)) { ++skipped; continue; }
-                        for (int c = 0; c < g.C; ++c)
-                            for (int v = 0; v < g.S; ++v) {
-                                int ih = oh * g.P - g.pad_h + v;
-                                if (ih < 0 || ih >= g.H) continue;
-                                for (int u = 0; u < g.R; ++u) {
-                                    int iw = ow * g.O - g.pad_w + u;
-                                    if (iw < 0 || iw >= g.W) continue;
-                                    dw[W_AT(g, k, c, v, u)] +=
-                                        (double)x[X_AT(g, n, c, ih, iw)] * (double)d;
-                                }
-                            }
-                    }
+        const int64_t total = (int64_t)g.N * g.K * g.OH * g.OW;
+        for (int64_t e = 0; e < total; ++e) {
+            const float d = dy[e];
+            if (!(d != 0.0f)) { ++skipped; continue; }
+            const int ow = (int)(e % g.OW), oh = (int)(e / g.OW % g.OH);
+            const int k = (int)(e / ((int64_t)g.OW * g.OH) % g.K), n = (int)(e / ((int64_t)g.OW * g.OH * g.K));
+            const int nl = links_of_output_pixel(&g, oh, ow, l);
+            for (int i = 0; i < nl; ++i)
+                for (int c = 0; c < g.C; ++c)
+                    dw[W_AT(g, k, c, l[i].v, l[i].u)] += (double)x[X_AT(g, n, c, l[i].ph, l[i].pw)] * (double)d;
+        }
     }
     if (n_skipped) *n_skipped = skipped;
     return 0;

@@ -359,3 +359,71 @@ def test_pins_detect_planted_mistakes():
     assert not np.allclose(_variant_fwd(g, x, w, flip=True), y, atol=1e-3)
     assert not np.allclose(_variant_fwd(g, x, w, swap_rs=True), y, atol=1e-3)
     assert not np.allclose(_variant_fwd(g, x, w, drop_pad=True), y, atol=1e-3)
+
+
+# ---------------------------------------------------------------------------
+# the checker itself: every GPU verdict goes through st_ref.rel_err, so it is pinned by cases
+# worked by hand and by deviations planted here (never in the oracle's convolutions)
+# ---------------------------------------------------------------------------
+def test_rel_err_hand_computed():
+    ref = np.array([1.0, 2.0, -3.0, 0.0])
+    scale = np.array([2.0, 4.0, 3.0, 0.0])
+    assert st_ref.rel_err(ref.copy(), ref, scale) == (0.0, 0)
+    got = np.array([1.5, 2.0, -3.0, 0.0])           # |1.5 - 1| / 2
+    assert st_ref.rel_err(got, ref, scale) == (0.25, 0)
+    got = np.array([1.0, 2.0, 3.0, -0.0])           # sign flipped: |3 + 3| / 3; -0 is a zero
+    assert st_ref.rel_err(got, ref, scale) == (2.0, 0)
+    got = np.array([1.0, 2.0, -3.0, 1e-30])         # all terms zero, value not zero
+    assert st_ref.rel_err(got, ref, scale) == (0.0, 1)
+
+
+def test_rel_err_is_per_element_not_global():
+    """A deviation is measured against the scale of its own element: a large neighbour hides nothing."""
+    ref = np.array([1e6, 1e-3])
+    scale = np.array([2e6, 2e-3])
+    got = np.array([1e6, 1e-3 + 2e-3 * 3e-4])
+    err, bad = st_ref.rel_err(got, ref, scale)
+    assert bad == 0 and err == pytest.approx(3e-4, rel=1e-9)
+
+
+def test_rel_err_flags_planted_deviation_on_a_real_layer():
+    """One element of an fp32 copy of the oracle's result moved by 2e-4 of its scale must be reported
+    at that size (the GPU tests' bar is 1e-4), one moved by 0.5e-4 must pass, and the unperturbed
+    copy stays at fp32 rounding."""
+    g = Geom(2, 16, 16, 6, 7, 3, 3, 1, 1, 1, 1)
+    x, w = rand(g.x_shape, 0.5), rand(g.w_shape)
+    y, ya = st_ref.conv_fwd(g, x, w)
+    got = y.astype(np.float32)
+    err0, bad0 = st_ref.rel_err(got, y, ya)
+    assert bad0 == 0 and err0 < 2.0 ** -23
+    idx = (1, 5, 3, 2)
+    assert ya[idx] > 0
+    for rel, must_pass in ((2e-4, False), (0.5e-4, True)):
+        bent = got.astype(np.float64)
+        bent[idx] = y[idx] + rel * ya[idx]
+        err, bad = st_ref.rel_err(bent, y, ya)
+        assert bad == 0 and err == pytest.approx(rel, rel=1e-6)
+        assert (err <= 1e-4) == must_pass
+
+
+def test_rel_err_flags_non_finite_and_unwritten_zero_rows():
+    g = Geom(1, 16, 16, 4, 4, 3, 3, 1, 1, 1, 1)
+    x, w = rand(g.x_shape), rand(g.w_shape)
+    x[0, :, :, :] = 0.0                                  # every term of every output is zero
+    y, ya = st_ref.conv_fwd(g, x, w)
+    assert not ya.any() and not y.any()
+    got = np.zeros_like(y)
+    assert st_ref.rel_err(got, y, ya) == (0.0, 0)
+    got[0, 3, 1, 1] = 1e-20
+    got[0, 4, 2, 2] = np.nan
+    assert st_ref.rel_err(got, y, ya) == (0.0, 2)
+    x2 = rand(g.x_shape)
+    y2, ya2 = st_ref.conv_fwd(g, x2, w)
+    bent = y2.copy()
+    bent[0, 0, 0, 0] = np.nan
+    err, _ = st_ref.rel_err(bent, y2, ya2)
+    assert err == float("inf")
+    bent[0, 0, 0, 0] = np.inf
+    assert st_ref.rel_err(bent, y2, ya2)[0] == float("inf")
+    with pytest.raises(ValueError):
+        st_ref.rel_err(y2[:, :1], y2, ya2)
