@@ -32,7 +32,21 @@
  * Inputs are read-only.  Buffers must not overlap.
  *
  * Errors: every entry point returns a status and never aborts, throws or
- * prints.  On any status other than ST_OK nothing has been enqueued.
+ * prints.  Arguments are checked on the host before anything is enqueued:
+ * descriptor, NULL and misaligned tensor pointers (ST_ERR_ALIGNMENT: the
+ * kernels use 16-byte vector accesses, which would fault), workspace.  With
+ * every status except ST_OK and ST_ERR_DEVICE nothing has been enqueued.
+ * ST_ERR_DEVICE means the HIP runtime refused one of the call's launches; a
+ * pass is up to seven launches (filter copy, sampling, main kernels, final
+ * sums), so earlier ones may already be in the stream: the contents of the
+ * output and of the workspace are then undefined.
+ *
+ * Limits (ST_ERR_UNSUPPORTED beyond them): H*W and OH*OW at most 2^27 - 1
+ * pixels, C*S*R (and K*S*R for the dy-testing BWW forms) at most 2^31 - 1,
+ * N at most 65535.
+ *
+ * The library reads no environment variables; kernel shapes and reduction
+ * splits depend on the descriptor alone.
  *
  * Numerics: products and sums are fp32; the summation order is unspecified
  * but fixed for a given shape (results are run-to-run deterministic; no
@@ -57,7 +71,8 @@ typedef enum {
     ST_ERR_BAD_SHAPE = 2,   /* non-positive dimension, C or K not a multiple of 16, empty output */
     ST_ERR_UNSUPPORTED = 3, /* a well-formed shape that no kernel covers */
     ST_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or smaller than st_conv_workspace_bytes */
-    ST_ERR_DEVICE = 5       /* the HIP runtime refused a launch */
+    ST_ERR_DEVICE = 5,      /* the HIP runtime refused a launch */
+    ST_ERR_ALIGNMENT = 6    /* a tensor pointer is not 64-byte aligned */
 } st_status;
 
 /* Convolution geometry, Table 1 of the paper plus explicit padding. */

@@ -608,6 +608,8 @@ constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are mult
 // stride-2 layers: 4x8 tiles keep the strided halo of the other operand (9x17 pixels x 64 channels) in LDS
 constexpr int kS2TH = 4, kS2TW = 8;
 
+constexpr int kBwwTargetWorkgroups = 512;
+
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 {
     BwwArgs A;
@@ -623,10 +625,8 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
     A.cgroups = ceil_div(d.C, 64);
     const int groups = ceil_div(d.K, 64) * A.cgroups;
     // number of partial sums: enough workgroups to fill the chip (256 compute units, 2 resident
-    // workgroups each); ST_BWW_WGS overrides the target (tuning aid)
-    const char *env = getenv("ST_BWW_WGS");
-    const int target = env ? atoi(env) : 512;
-    int splits = ceil_div(target > 0 ? target : 512, groups);
+    // workgroups each)
+    int splits = ceil_div(kBwwTargetWorkgroups, groups);
     if (splits > A.units) splits = A.units;
     if (splits < 1) splits = 1;
     A.splits = splits;
@@ -644,9 +644,7 @@ BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw)
     A.units = (int)chunks;                          // bww_fast_supported bounds N*H*W
     A.cgroups = ceil_div(d.C, cw);
     const int groups = ceil_div(d.K, kw) * A.cgroups;
-    const char *env = getenv("ST_BWW_WGS");
-    const int target = env ? atoi(env) : 512;
-    int splits = ceil_div(target > 0 ? target : 512, groups);
+    int splits = ceil_div(kBwwTargetWorkgroups, groups);
     if (splits > A.units) splits = A.units;
     if (splits < 1) splits = 1;
     A.splits = splits;

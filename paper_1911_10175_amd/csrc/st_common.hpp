@@ -14,6 +14,7 @@ namespace st {
 
 constexpr int kBlk = 16;        // channel block of the blocked layouts
 constexpr int kWave = 64;       // CDNA wavefront width
+constexpr int kMaxDevices = 64; // per-device set-up state is kept for this many devices of a process
 
 // Geometry of one correlation "act_out[n,ko,oh,ow] = sum act_in[n,ci,oh*P-ph+v,ow*O-pw+u] * f[ko,ci,v,u]".
 // FWD uses it directly; stride-1 BWI is the same correlation on dy with transposed, tap-reversed

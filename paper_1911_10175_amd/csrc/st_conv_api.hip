@@ -20,9 +20,10 @@ st_status validate(const st_conv_desc *d, Dims *o)
     if (d->H + 2 * d->pad_h < d->S || d->W + 2 * d->pad_w < d->R) return ST_ERR_BAD_SHAPE;
     o->OH = (d->H + 2 * d->pad_h - d->S) / d->stride_h + 1;
     o->OW = (d->W + 2 * d->pad_w - d->R) / d->stride_w + 1;
-    // the kernels index tensors with size_t but keep per-image pixel counts and grids in int
+    // the kernels index tensors with size_t but keep grids and offsets within one channel block of
+    // one image (16 floats per pixel) in int
     const long long lim = 0x7fffffffLL;
-    if ((long long)d->H * d->W > lim || (long long)o->OH * o->OW > lim) return ST_ERR_UNSUPPORTED;
+    if ((long long)d->H * d->W * st::kBlk > lim || (long long)o->OH * o->OW * st::kBlk > lim) return ST_ERR_UNSUPPORTED;
     if ((long long)d->C * d->S * d->R > lim || d->N > 65535) return ST_ERR_UNSUPPORTED;
     // padding at least as large as the filter would make whole output rows read only zeros;
     // legal, handled by the generic kernels
@@ -54,6 +55,15 @@ bool bwi_as_fwd(const st_conv_desc &d, const Dims &o, Geom *g)
     g->pw = d.R - 1 - d.pad_w; g->ph = d.S - 1 - d.pad_h;
     g->sel = nullptr; g->want = 0; g->thr = 0;
     return true;
+}
+
+// Tensor arguments: all present, each on a 64-byte boundary (one pixel's channel block; the kernels
+// move them with 16-byte vector loads and stores, which fault on a misaligned address).
+st_status tensors_ok(const void *a, const void *b, const void *c)
+{
+    if (!a || !b || !c) return ST_ERR_NULL;
+    if (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c) % 64 != 0) return ST_ERR_ALIGNMENT;
+    return ST_OK;
 }
 
 bool ws_ok(const void *ws, size_t have, size_t need)
@@ -114,7 +124,7 @@ st_status run_fwd(const st_conv_desc *d, const float *x, const float *w, float *
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
-    if (!x || !w || !y) return ST_ERR_NULL;
+    if ((rc = tensors_ok(x, w, y)) != ST_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Geom g = fwd_geom(*d, o);
     if (dense) {
@@ -138,7 +148,7 @@ st_status run_bwi(const st_conv_desc *d, const float *dy, const float *w, float 
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
-    if (!dy || !w || !dx) return ST_ERR_NULL;
+    if ((rc = tensors_ok(dy, w, dx)) != ST_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     Geom g;
     const bool fast = bwi_as_fwd(*d, o, &g) &&
@@ -162,7 +172,7 @@ st_status run_bww(const st_conv_desc *d, const float *x, const float *dy, float 
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
-    if (!x || !dy || !dw) return ST_ERR_NULL;
+    if ((rc = tensors_ok(x, dy, dw)) != ST_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!st::bww_fast_supported(*d)) return dev(st::launch_generic_bww(*d, x, dy, dw, !dense, s));
     const size_t need = dense ? st::bww_dense_workspace(*d) : st::bww_sparse_workspace(*d);
@@ -178,7 +188,7 @@ st_status run_bww_dy(const st_conv_desc *d, const float *x, const float *dy, flo
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
-    if (!x || !dy || !dw) return ST_ERR_NULL;
+    if ((rc = tensors_ok(x, dy, dw)) != ST_OK) return rc;
     if ((long long)d->K * d->S * d->R > 0x7fffffffLL) return ST_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!st::bww_dy_fast_supported(*d)) return dev(st::launch_generic_bww_dy(*d, x, dy, dw, s));
@@ -197,7 +207,7 @@ st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float 
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
-    if (!act || !w || !out) return ST_ERR_NULL;
+    if ((rc = tensors_ok(act, w, out)) != ST_OK) return rc;
     const int pass = bwi ? ST_PASS_BWI_AUTO : ST_PASS_FWD_AUTO, base = bwi ? ST_PASS_BWI : ST_PASS_FWD;
     if (!ws_ok(ws, ws_bytes, workspace_bytes(*d, o, pass, false))) return ST_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -257,7 +267,7 @@ st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, f
     Dims o;
     st_status rc = validate(d, &o);
     if (rc != ST_OK) return rc;
-    if (!x || !dy || !dw) return ST_ERR_NULL;
+    if ((rc = tensors_ok(x, dy, dw)) != ST_OK) return rc;
     if ((long long)d->K * d->S * d->R > 0x7fffffffLL) return ST_ERR_UNSUPPORTED;
     if (!ws_ok(ws, ws_bytes, workspace_bytes(*d, o, ST_PASS_BWW_AUTO, false))) return ST_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -378,10 +388,11 @@ const char *st_status_str(st_status status)
     case ST_ERR_UNSUPPORTED: return "shape not supported by any kernel";
     case ST_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case ST_ERR_DEVICE: return "HIP launch failed";
+    case ST_ERR_ALIGNMENT: return "a tensor pointer is not 64-byte aligned";
     default: return "unknown status";
     }
 }
 
-const char *st_conv_version(void) { return "0.5"; }
+const char *st_conv_version(void) { return "0.6"; }
 
 }  // extern "C"

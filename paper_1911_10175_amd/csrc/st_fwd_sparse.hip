@@ -16,7 +16,6 @@
 //    reused by every non-zero pixel of the tile; they stream from L2 out of a copy of the filters
 //    in wavefront order ([Ko/64][Ci][S][R][64 k], written before every launch), 256 contiguous
 //    bytes per load instruction.
-#include <cstdlib>
 #include <type_traits>
 
 #include "st_common.hpp"
@@ -350,8 +349,7 @@ hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out,
 // Picks the channel split: layers with few tiles get 2, 4, 8 or 16 wavefronts per task so that the chip
 // (1024 SIMDs x 4 resident wavefronts) is filled and the tail is short: a wavefront walks its share
 // of the input channels one after the other, about 1.7 us per channel, so a launch that leaves
-// half the wavefront slots empty is as slow as one that fills them.  ST_FWD_SPARSE_CS overrides
-// (tuning aid).
+// half the wavefront slots empty is as slow as one that fills them.
 template <int R, int S, int TH, int TW, int KPL, int MINW, int SD = 1, int SU = 1, int OFF = 0>
 hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
 {
@@ -364,11 +362,6 @@ hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out
     if ((CiB >= 16 || tasks < 3072) && CiB % 4 == 0) cs = 4;
     if (deep && tasks <= 512 && CiB % 8 == 0) cs = 8;
     if (deep && tasks <= 256 && CiB % 16 == 0) cs = 16;
-    const char *env = getenv("ST_FWD_SPARSE_CS");
-    if (env) {
-        const int e = atoi(env);
-        if ((e == 1 || e == 2 || e == 4 || (deep && (e == 8 || e == 16))) && CiB % e == 0) cs = e;
-    }
     if constexpr (deep) {
         if (cs == 16) return launch_cs<R, S, TH, TW, KPL, MINW, 16, SD, SU, OFF>(g, in, f, out, s);
         if (cs == 8) return launch_cs<R, S, TH, TW, KPL, MINW, 8, SD, SU, OFF>(g, in, f, out, s);

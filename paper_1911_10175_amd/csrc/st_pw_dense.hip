@@ -282,9 +282,20 @@ hipError_t launch_pw_lds(const Geom &g, bool transpose, const float *in, const f
     long long blocks = 512;
     if (blocks * 4 > ntiles) blocks = (ntiles + 3) / 4;
     auto kern = pw_dense_lds_kernel<KB, 4>;
+    // More than 48 KB of dynamic LDS has to be allowed once per kernel and device; done on the first
+    // call on that device (with 64 KB, the most a supported filter matrix takes), outside any launch
+    // sequence a caller may be capturing into a graph later.
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static bool allowed[kMaxDevices] = {};
+        int devid = 0;
+        hipError_t e = hipGetDevice(&devid);
         if (e != hipSuccess) return e;
+        if (devid < 0 || devid >= kMaxDevices) return hipErrorInvalidDevice;
+        if (!allowed[devid]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+            if (e != hipSuccess) return e;
+            allowed[devid] = true;
+        }
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), lds, s, (int)total_px, HW, CiB, g.Ko / kBlk, in, w,
                        transpose ? 1 : 0, out, g.sel, g.thr);
@@ -328,8 +339,6 @@ hipError_t launch_pw_dense(const Geom &g, const float *in, const float *wd, floa
             const long long waves = (total_px + 32 * c[0] - 1) / (32 * c[0]) * ceil_div(g.Ko, 32 * c[1]);
             if (waves >= 768) { pb = c[0]; kb = c[1]; break; }
         }
-    const char *env = getenv("ST_PW_DENSE_CFG");        // tuning aid: "PB KB" digits, e.g. "24"
-    if (env && env[0] && env[1]) { pb = env[0] - '0'; kb = env[1] - '0'; }
     if (kb == 1) return pb == 1 ? launch_pw<1, 1, 4>(g, in, wd, out, s) : launch_pw<2, 1, 4>(g, in, wd, out, s);
     if (kb == 2) return pb == 1 ? launch_pw<1, 2, 4>(g, in, wd, out, s) : launch_pw<2, 2, 4>(g, in, wd, out, s);
     return pb == 1 ? launch_pw<1, 4, 3>(g, in, wd, out, s) : launch_pw<2, 4, 3>(g, in, wd, out, s);

@@ -29,8 +29,8 @@ def test_header_symbols_are_exported():
 
 def test_status_strings_and_version():
     assert st.st_status_str(0) == "ok"
-    seen = {st.st_status_str(i) for i in range(6)}
-    assert len(seen) == 6 and all(seen)
+    seen = {st.st_status_str(i) for i in range(7)}
+    assert len(seen) == 7 and all(seen)
     assert st.st_status_str(99) == "unknown status"
     assert re.fullmatch(r"\d+\.\d+", st.st_conv_version())
 
@@ -60,6 +60,33 @@ def test_validation_happens_on_the_host():
     with pytest.raises(st.StConvError) as e:
         st.st_conv_fwd(bad[0], 256, 256, 256)
     assert e.value.status == 2
+
+
+def test_misaligned_tensors_and_oversized_images_are_refused_on_the_host():
+    """The kernels use 16-byte vector accesses and keep offsets within one image's channel block in
+    int: both limits are statuses, never faults."""
+    d = st.ConvDesc(1, 16, 16, 8, 8, 3, 3, 1, 1, 1, 1)
+    fns = (st.st_conv_fwd, st.st_conv_fwd_dense, st.st_conv_bwi, st.st_conv_bwi_dense, st.st_conv_bww,
+           st.st_conv_bww_dense, st.st_conv_bww_dy, st.st_conv_bww_auto, st.st_conv_fwd_auto, st.st_conv_bwi_auto)
+    for fn in fns:
+        for args in ((256 + 4, 256, 256), (256, 256 + 16, 256), (256, 256, 256 + 32)):
+            assert fn(d, *args, ws=4096, ws_bytes=1 << 30, check=False) == 6, fn
+        assert fn(d, 256, None, 256 + 4, check=False) == 1          # NULL is reported before alignment
+    assert "aligned" in st.st_status_str(6)
+    # 2^27 pixels per image: (h*W + w) * 16 no longer fits an int
+    big = st.ConvDesc(1, 16, 16, 1 << 14, 1 << 13, 1, 1)
+    ok = st.ConvDesc(1, 16, 16, (1 << 14) - 1, 1 << 13, 1, 1)
+    for fn in fns:
+        assert fn(big, 256, 256, 256, ws=4096, ws_bytes=1 << 40, check=False) == 3, fn
+    assert st.st_conv_workspace_bytes(big, st.ST_PASS_BWW) == 0
+    assert st.st_conv_sparse_threshold(ok, st.ST_PASS_FWD) >= 0 and st.st_conv_sparse_threshold(big, st.ST_PASS_FWD) == -1
+
+
+def test_library_reads_no_environment_variables():
+    """Kernel shapes, reduction splits and workspace sizes depend on the descriptor alone."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--undefined-only", st.lib_path()], capture_output=True, text=True, check=True).stdout
+    assert "getenv" not in out
 
 
 def test_workspace_query_and_rejection():

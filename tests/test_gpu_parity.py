@@ -127,13 +127,15 @@ def test_sparse_equals_dense_control_and_is_deterministic():
         assert np.allclose(a, c, rtol=1e-3, atol=1e-4)
 
 
-@pytest.mark.parametrize("cs", [1, 2, 4, 8, 16])
-def test_fwd_bwi_channel_split_override(cs, monkeypatch):
-    """Every channel split of the zero-skipping FWD / BWI kernel (normally chosen from the number of
-    tasks of the launch; ST_FWD_SPARSE_CS forces one) gives the oracle's result on ragged tiles."""
-    g = Geom(2, 256, 256, 10, 13, 3, 3, 1, 1, 1, 1)
+@pytest.mark.parametrize("cs,ch", [(1, 48), (2, 96), (4, 64), (8, 128), (16, 256)])
+def test_fwd_bwi_channel_split(cs, ch):
+    """Every channel split of the zero-skipping FWD / BWI kernel gives the oracle's result on ragged
+    tiles.  The split follows from the descriptor alone: with C = K = ch and this few tiles a task is
+    shared by the largest power of two <= 16 that divides ch / 16 wavefronts, each reducing that share
+    of the input channels (1 for 3 blocks, 2 for 6, 4 for 4, 8 for 8, 16 for 16)."""
+    g = Geom(2, ch, ch, 10, 13, 3, 3, 1, 1, 1, 1)
+    assert (ch // 16) % cs == 0 and (cs == 16 or (ch // 16) % (2 * cs) != 0)
     x, w, dy = synth(g, 0.6, 0.5, seed=31 + cs)
-    monkeypatch.setenv("ST_FWD_SPARSE_CS", str(cs))
     check_all_passes_full(g, x, w, dy, f"split {cs}", passes=("fwd", "bwi"), variants=(False,))
 
 
