@@ -19,6 +19,8 @@ bits do not depend on numpy's or torch's generator version.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
 import numpy as np
@@ -50,26 +52,48 @@ def _uniform_block(key: np.uint64, start: int, count: int, draw: int) -> np.ndar
     return (h >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
 
 
+def _workers() -> int:
+    """Threads used to draw large tensors: the chunks of a counter-based stream are independent, so the
+    bits do not depend on this number."""
+    try:
+        return max(1, min(16, len(os.sched_getaffinity(0))))
+    except AttributeError:
+        return max(1, min(16, os.cpu_count() or 1))
+
+
+def _fill(out: np.ndarray, chunk_fn) -> np.ndarray:
+    n = out.size
+    starts = range(0, n, _CHUNK)
+
+    def one(s):
+        c = min(_CHUNK, n - s)
+        out[s:s + c] = chunk_fn(s, c)
+
+    if len(starts) <= 1 or _workers() == 1:
+        for s in starts:
+            one(s)
+    else:
+        with ThreadPoolExecutor(max_workers=_workers()) as pool:
+            list(pool.map(one, starts))
+    return out
+
+
 def uniform(stream: int, n: int) -> np.ndarray:
     """n fp64 uniforms in [0,1)."""
     key = _key(stream)
-    out = np.empty(n, dtype=np.float64)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
-        out[s:s + c] = _uniform_block(key, s, c, 0)
-    return out
+    return _fill(np.empty(n, dtype=np.float64), lambda s, c: _uniform_block(key, s, c, 0))
 
 
 def normal(stream: int, n: int) -> np.ndarray:
     """n fp64 standard normals (Box-Muller on two uniforms per element)."""
     key = _key(stream)
-    out = np.empty(n, dtype=np.float64)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
+
+    def chunk(s, c):
         u1 = 1.0 - _uniform_block(key, s, c, 0)          # (0,1]
         u2 = _uniform_block(key, s, c, 1)
-        out[s:s + c] = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-    return out
+        return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+
+    return _fill(np.empty(n, dtype=np.float64), chunk)
 
 
 def relu_threshold(p: float) -> float:
@@ -77,24 +101,35 @@ def relu_threshold(p: float) -> float:
     return float(ndtri(p))
 
 
-def relu_sparse(shape, p: float, stream: int) -> np.ndarray:
-    """fp32 tensor max(0, z - t); p = 0 returns the unclamped Gaussian (no zeros)."""
-    n = int(np.prod(shape))
-    z = normal(stream, n)
+def relu_from_normal(z: np.ndarray, p: float) -> np.ndarray:
+    """fp32 max(0, z - t) for fp64 standard normals z; p = 0 returns the unclamped Gaussian (no zeros).
+    The subtraction and the clamp are done in fp64, then rounded once to fp32."""
     if p <= 0.0:
-        return z.astype(np.float32).reshape(shape)
-    t = relu_threshold(p)
-    return np.maximum(0.0, z - t).astype(np.float32).reshape(shape)
+        return z.astype(np.float32)
+    return np.maximum(0.0, z - relu_threshold(p)).astype(np.float32)
+
+
+def relu_sparse(shape, p: float, stream: int) -> np.ndarray:
+    """fp32 tensor max(0, z - t); p = 0 returns the unclamped Gaussian (no zeros).  The normals drawn
+    depend on the stream only, not on p: tensors of one stream at several p share their z."""
+    return relu_from_normal(normal(stream, int(np.prod(shape))), p).reshape(shape)
+
+
+def mask_from_uniform(g: np.ndarray, u: np.ndarray, q: float) -> np.ndarray:
+    """fp32 g * m for fp64 normals g and uniforms u, m = (u >= q): masked negatives become -0.0."""
+    g = g.astype(np.float32)
+    if q <= 0.0:
+        return g
+    return g * (u >= q).astype(np.float32)
 
 
 def bernoulli_masked(shape, q: float, stream_g: int, stream_m: int) -> np.ndarray:
     """fp32 tensor g * m with m = 1 with probability 1-q.  Masked negatives become -0.0."""
     n = int(np.prod(shape))
-    g = normal(stream_g, n).astype(np.float32)
+    g = normal(stream_g, n)
     if q <= 0.0:
-        return g.reshape(shape)
-    m = (uniform(stream_m, n) >= q).astype(np.float32)
-    return (g * m).reshape(shape)
+        return g.astype(np.float32).reshape(shape)
+    return mask_from_uniform(g, uniform(stream_m, n), q).reshape(shape)
 
 
 def dead_channels(a: np.ndarray, p_dead: float, stream: int) -> np.ndarray:

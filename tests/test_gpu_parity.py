@@ -393,20 +393,22 @@ def test_config3_resnet3_2_full():
     check_all_passes_full(g, x, w, dy, "config3")
 
 
-def test_config2_vgg3_2_sampled():
-    """The benchmark workload at full size (N=16, 256->256 @56x56), sampled outputs."""
+def test_config2_vgg3_2_full():
+    """The vgg3_2-shaped workload at full size (N=16, 256->256 @56x56, x 60 % / dy 50 % zeros): every
+    element of y, dx and dw of every entry point against the oracle."""
     L = stgen.VGG3_2_N16
     g = geom_of(L)
     x, w, dy = stgen.make_layer_tensors(L, seed=0)
     assert abs(stgen.zero_fraction(x) - 0.6) < 0.002 and abs(stgen.zero_fraction(dy) - 0.5) < 0.002
-    check_all_passes_sampled(g, x, w, dy, "config2")
+    check_all_passes_full(g, x, w, dy, "config2")
 
 
 @pytest.mark.parametrize("layer", stgen.BOTTLENECK, ids=[l.name for l in stgen.BOTTLENECK])
-def test_config4_bottleneck_sampled(layer):
+def test_config4_bottleneck_full(layer):
+    """The three layers of the ResNet-50 bottleneck at N=32, every element of every output."""
     g = geom_of(layer)
     x, w, dy = stgen.make_layer_tensors(layer, seed=0)
-    check_all_passes_sampled(g, x, w, dy, "config4-" + layer.name, n_samples=2048, n_bww=256)
+    check_all_passes_full(g, x, w, dy, "config4-" + layer.name)
 
 
 VGG_SMALL = [l for l in stgen.vgg16_stack(0.5) if l.H <= 28]
@@ -490,3 +492,27 @@ def test_config5_sweep_levels_on_vgg5(p):
     g = geom_of(layer)
     x, w, dy = stgen.make_layer_tensors(layer, seed=2)
     check_all_passes_sampled(g, x, w, dy, f"vgg5_3 p={p}", n_samples=2048, n_bww=256)
+
+
+# One layer of each tile configuration of the 3x3 kernels (64 produced channels: 8x8 tiles, one channel
+# per lane, in FWD and BWI of vgg1_2 and in BWI of vgg2_1; multiples of 128: 4x8 tiles, two per lane;
+# rows of 28 and 14 pixels: 7-wide tiles) at the full minibatch and at every swept zero fraction.
+SWEEP_LAYERS = ("vgg1_2", "vgg2_1", "vgg3_2", "vgg4_2", "vgg5_1")
+
+
+@pytest.mark.parametrize("name", SWEEP_LAYERS)
+def test_config5_all_sweep_levels_full_batch_sampled(name):
+    """N=32, zero fraction of x and of dy swept over {0, 30, 50, 70, 90} %: the tensors of one stream
+    at several fractions share their normals and uniforms, which are drawn once."""
+    layer = [l for l in stgen.vgg16_stack(0.5) if l.name == name][0]
+    g = geom_of(layer)
+    seed = 40 + SWEEP_LAYERS.index(name)
+    z = stgen.normal(4 * seed, int(np.prod(g.x_shape)))
+    w = stgen.he_normal(g.w_shape, 4 * seed + 1)
+    gn = stgen.normal(4 * seed + 2, int(np.prod(g.y_shape)))
+    u = stgen.uniform(4 * seed + 3, int(np.prod(g.y_shape)))
+    for p in (0.0, 0.3, 0.5, 0.7, 0.9):
+        x = stgen.relu_from_normal(z, p).reshape(g.x_shape)
+        dy = stgen.mask_from_uniform(gn, u, p).reshape(g.y_shape)
+        assert abs(stgen.zero_fraction(x) - p) < 0.002 and abs(stgen.zero_fraction(dy) - p) < 0.002
+        check_all_passes_sampled(g, x, w, dy, f"config5-{name}-p{p}", n_samples=1024, n_bww=64, seed=int(100 * p))

@@ -30,3 +30,15 @@ def test_filter_layout_formula():
     t = torch.from_numpy(f)
     assert torch.equal(pack_filters(t), torch.from_numpy(pack_filters(f)))
     assert torch.equal(unpack_filters(pack_filters(t)), t)
+
+
+def test_harness_gathers_index_the_blocked_layouts():
+    """The GPU tests pick sampled outputs straight out of blocked device tensors: the index arithmetic
+    they use must agree with unpacking the whole tensor (run here on CPU tensors)."""
+    from tests.gpu_harness import gather_activations, gather_filters, sample_coords
+    a = np.random.default_rng(0).standard_normal((2, 48, 5, 7)).astype(np.float32)
+    ca = sample_coords(a.shape, 200, 1)
+    assert (gather_activations(torch.from_numpy(pack_activations(a)), ca) == a[tuple(ca.T)]).all()
+    f = np.random.default_rng(1).standard_normal((32, 48, 3, 2)).astype(np.float32)
+    cf = sample_coords(f.shape, 200, 2)
+    assert (gather_filters(torch.from_numpy(pack_filters(f)), cf) == f[tuple(cf.T)]).all()
