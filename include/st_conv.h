@@ -186,6 +186,23 @@ st_status st_conv_bwi_auto(const st_conv_desc *desc, const float *dy, const floa
                            void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * st_conv_fwd for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same tensors, same kernels
+ * and bit-identical results as st_conv_fwd; the filter copy that st_conv_fwd writes into the caller's
+ * workspace goes into a 16 MiB array built into the library's device image instead (one copy per GPU
+ * the library runs on, held until the process ends).  The call allocates and frees nothing and does
+ * not synchronise.  Geometries whose filter copy st_conv_workspace_bytes(desc, ST_PASS_FWD, 0)
+ * exceeds 16 MiB (16777216 bytes) are refused with ST_ERR_WORKSPACE before anything is enqueued.
+ * The first call on a device looks up the array's device address (ST_ERR_DEVICE if the runtime
+ * refuses); make that call outside a graph capture.  All calls on one GPU share the one array, which
+ * keeps the last call's filter copy: nothing in it has to start at zero (every element a launch
+ * reads is written by the same call first), but two calls in flight at the same time on one GPU
+ * - on different streams or from different threads - race on it and must be serialised by the caller.
+ */
+st_status st_conv_fwd_static(const st_conv_desc *desc, const float *x, const float *w, float *y,
+                             void *hip_stream);
+
+/*
  * Bytes of device workspace the given pass needs for this geometry
  * (pass = ST_PASS_*, dense = 0 for st_conv_<pass>, 1 for st_conv_<pass>_dense; ST_PASS_BWW_DY with
  * dense = 0 is st_conv_bww_dy, ST_PASS_*_AUTO with dense = 0 are the st_conv_*_auto entry points).

@@ -18,7 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libst_conv.so"
 EXPORTS = ("st_conv_fwd", "st_conv_fwd_dense", "st_conv_bwi", "st_conv_bwi_dense", "st_conv_bww",
            "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_fwd_auto", "st_conv_bwi_auto",
-           "st_conv_workspace_bytes", "st_conv_sparse_threshold", "st_status_str", "st_conv_version")
+           "st_conv_workspace_bytes", "st_conv_sparse_threshold", "st_status_str", "st_conv_version",
+           "st_conv_fwd_static")
 
 
 class StConvError(RuntimeError):
@@ -86,6 +87,8 @@ def load_library():
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.POINTER(_CDesc), p, p, p, p, ctypes.c_size_t, p]
             fn.restype = ctypes.c_int
+        lib.st_conv_fwd_static.argtypes = [ctypes.POINTER(_CDesc), p, p, p, p]
+        lib.st_conv_fwd_static.restype = ctypes.c_int
         lib.st_conv_workspace_bytes.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int, ctypes.c_int]
         lib.st_conv_workspace_bytes.restype = ctypes.c_size_t
         lib.st_conv_sparse_threshold.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int]
@@ -188,3 +191,13 @@ def st_conv_fwd_auto(desc, x, w, y, ws=None, stream=None, ws_bytes=None, check=T
 
 def st_conv_bwi_auto(desc, dy, w, dx, ws=None, stream=None, ws_bytes=None, check=True):
     return _call("st_conv_bwi_auto", desc, dy, w, dx, ws, ws_bytes, stream, check)
+
+
+def st_conv_fwd_static(desc, x, w, y, stream=None, check=True):
+    """st_conv_fwd without a workspace argument (built-in 16 MiB scratch; allocates nothing)."""
+    lib = load_library()
+    c = desc._c()
+    rc = lib.st_conv_fwd_static(ctypes.byref(c), _addr(x), _addr(w), _addr(y), _stream(stream))
+    if check and rc != ST_OK:
+        raise StConvError(rc, st_status_str(rc))
+    return rc

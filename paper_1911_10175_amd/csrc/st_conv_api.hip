@@ -1,6 +1,15 @@
 // C ABI of the library (include/st_conv.h): argument validation and kernel selection.
 // No allocation, no synchronisation, no printing happens here.
+#include <mutex>
+
 #include "st_common.hpp"
+
+// Built-in scratch of st_conv_fwd_static (callers that cannot allocate): the filter copy in wavefront
+// order that st_conv_fwd otherwise writes into the caller's workspace.  One copy per GPU the library
+// runs on, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: kernels are given the device address obtained from it, never the name.
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / sizeof(float)];
 
 namespace {
 
@@ -294,9 +303,44 @@ st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, f
     return dev(st::launch_bww_dense(*d, x, dy, dw, part, s, sel));
 }
 
+// Device address of the built-in scratch array on the current device, looked up on the first call on
+// that device and kept; nullptr (with *err set) if the runtime refuses.
+float *static_scratch(hipError_t *err)
+{
+    static std::mutex lock;
+    static float *ptr[st::kMaxDevices] = {};
+    int devid = 0;
+    *err = hipGetDevice(&devid);
+    if (*err != hipSuccess) return nullptr;
+    if (devid < 0 || devid >= st::kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> hold(lock);
+    if (!ptr[devid]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !p) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+        ptr[devid] = static_cast<float *>(p);
+    }
+    return ptr[devid];
+}
+
 }  // namespace
 
 extern "C" {
+
+st_status st_conv_fwd_static(const st_conv_desc *desc, const float *x, const float *w, float *y, void *hip_stream)
+{
+    Dims o;
+    st_status rc = validate(desc, &o);
+    if (rc != ST_OK) return rc;
+    if ((rc = tensors_ok(x, w, y)) != ST_OK) return rc;
+    const size_t need = workspace_bytes(*desc, o, ST_PASS_FWD, false);
+    if (need > kStaticScratchBytes) return ST_ERR_WORKSPACE;
+    if (need == 0) return run_fwd(desc, x, w, y, nullptr, 0, hip_stream, false);
+    hipError_t e;
+    float *ws = static_scratch(&e);
+    if (!ws) return ST_ERR_DEVICE;
+    return run_fwd(desc, x, w, y, ws, kStaticScratchBytes, hip_stream, false);
+}
 
 st_status st_conv_fwd(const st_conv_desc *desc, const float *x, const float *w, float *y, void *ws,
                       size_t ws_bytes, void *hip_stream)
