@@ -1,15 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the zero-skipping convolution passes on one MI355X.
 
-A step is one pass of the whole hot path -- st_conv_fwd, st_conv_bwi, st_conv_bww -- over one
-batch of the VGG16 conv3_2-shaped layer (N=16, C=K=256, 56x56, 3x3, stride 1, pad 1) with
-synthetic inputs: x = ReLU-shifted Gaussian with 60 % zeros, dy = Bernoulli-masked Gaussian with
-50 % zeros, He-normal filters.  Inputs are resident in HBM before the timed region.
+Workload: the VGG16 non-initial convolution stack of the paper's Table 1 at minibatch 32 (twelve 3x3
+layers, stride 1, pad 1: 64-64 @224, 64-128 @112, 128-128 @112, 128-256 @56, 256-256 @56 x2,
+256-512 @28, 512-512 @28 x2, 512-512 @14 x3) with synthetic inputs: x = ReLU-shifted Gaussian,
+dy = Bernoulli-masked Gaussian, He-normal filters, the zero fraction of x and of dy swept over
+{0, 30, 50, 70, 90} % (the experiment of Sec. 5.1 / Table 3 of the paper, which used minibatch 16).
 
-Prints ONE JSON line.  value = effective (dense-equivalent) TFLOP/s of the step,
-3 * 2*N*K*C*OH*OW*R*S / step time.  Extra objects: per-pass timings of the sparse entry points and
-of the dense controls, the sparse-over-dense speedup at 0/30/50/70/90 % zeros, the roofline of the
-dominant kernel, and the CPU oracle timed on a bounded sample of the same workload.
+A step is one pass of the whole hot path -- st_conv_fwd, st_conv_bwi, st_conv_bww of every layer of the
+stack -- at the headline zero fraction (--level, default 50 %), all tensors resident in HBM before the
+timed region.  Prints ONE JSON line.  value = effective (dense-equivalent) TFLOP/s of the step,
+3 * sum_layers 2*N*K*C*OH*OW*R*S / step time.  Extra objects: "sweep" (per zero fraction: time of the
+zero-skipping entry points and of the dense controls per layer and pass, and the stack's speed-up),
+"roofline" (the kernel that takes most of the step), "cpu_baseline" (the CPU oracle on one image of
+every layer), "other_configs" (the single-layer workloads of the benchmark definition, the 1x1 layers
+also with cold caches).
 """
 import argparse
 import json
@@ -21,132 +26,206 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_FP32_VECTOR = 157.3      # TFLOP/s, published MI355X fp32 vector peak (needs packed fp32 math)
-PEAK_FP32_FMA = 78.6          # TFLOP/s, 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz: one v_fma_f32 per lane-clock
-PEAK_FP32_MFMA = 157.3        # TFLOP/s, published dense fp32 matrix peak
+# MI355X peaks (TFLOP/s).  fp32 vector: 256 CU x 4 SIMD x 32 lanes/clk x 2 flop x 2.4 GHz; a stream of
+# independent v_fmac_f32 from two or more wavefronts per SIMD measures 141 TFLOP/s (one wave-wide
+# instruction every 2 cycles at the ~2.15 GHz the chip sustains under that load; see
+# profiles/valu_fma_rate.md), so the published figure is the ceiling of plain, unpacked FMAs too.
+PEAK_FP32_VECTOR = 157.3
+PEAK_FP32_MFMA = 157.3
+PEAK_HBM_TBS = 8.0
+LEVELS = (0.0, 0.3, 0.5, 0.7, 0.9)
+CPU_IMAGES = 4          # images per layer the CPU oracle is timed on (of the minibatch of 32): 10-20 s of work
 
-# HBM traffic per launch of the dominant kernel (fwd_sparse_kernel on this workload) from two
-# rocprofv3 --pmc runs, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 (factors from a 256 MiB copy of known
-# size): 47712.9 KiB * 2 + 50176.0 KiB.  See profiles/bench_vgg3_2_hbm_traffic.md.
-MEASURED_TRAFFIC_BYTES = int((47712.9 * 2.0 + 50176.0) * 1024)
 
-
-def sustain(fn, ms, stream):
+def sustain(fn, ms):
     """Keeps the GPU busy with fn for about ms milliseconds (untimed).  After an idle spell of 50 ms or
-    more the chip needs some 30 ms of continuous work to return to its sustained clocks (the same launch
-    reads 0.46 ms right after a pause and 0.40 ms from then on); every timing below starts from that state,
-    which is the one a training run is in."""
+    more the chip needs some 30 ms of continuous work to return to its sustained clocks; every timing
+    below starts from that state, which is the one a training run is in."""
     import torch
     t0 = time.perf_counter()
     while True:
-        for _ in range(4):
+        for _ in range(2):
             fn()
         torch.cuda.current_stream().synchronize()
         if (time.perf_counter() - t0) * 1e3 >= ms:
             return
 
-def write_config_table(path, st, stgen, torch, dev, stream, sustain_ms=30.0):
-    """Per (layer, zero fraction, pass): sparse and dense time, effective TFLOP/s, executed TFLOP/s as a
-    fraction of the fp32 vector peak, dense fraction of the MFMA peak, speed-up.  Inputs are drawn on the
-    device (torch generator, seed 0) with the same distributions as stgen: timing only, no parity."""
-    import math
 
-    torch.manual_seed(0)
+def time_call(fn, iters, sustain_ms, stream):
+    """(median, mean) milliseconds of fn over iters launches, HIP events on the launch stream."""
+    import torch
+    sustain(fn, sustain_ms)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in evs:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], sum(ts) / len(ts)
 
-    def relu_sparse(shape, p):
-        z = torch.randn(shape, device=dev)
-        if p <= 0:
-            return z
-        t = math.sqrt(2.0) * torch.erfinv(torch.tensor(2.0 * p - 1.0, dtype=torch.float64)).item()
-        return torch.clamp(z - t, min=0)
 
-    def masked(shape, q):
-        g = torch.randn(shape, device=dev)
-        return g if q <= 0 else g * (torch.rand(shape, device=dev) >= q)
+class LayerOnDevice:
+    """One layer: the random draws behind x and dy (fp64, blocked layout) stay on the device, so that the
+    tensors of any zero fraction are one elementwise pass away; outputs and workspaces are allocated once."""
 
-    def timeit(fn, iters=7):
-        sustain(fn, sustain_ms, stream)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
-        for a, b in evs:
-            a.record(stream)
-            fn()
-            b.record(stream)
-        torch.cuda.synchronize()
-        ts = sorted(a.elapsed_time(b) for a, b in evs)
-        return ts[len(ts) // 2]
+    def __init__(self, layer, seed, st, stgen, torch, dev, keep_host_image=True):
+        import numpy as np
+        self.L, self.st, self.torch = layer, st, torch
+        L = layer
+        self.d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, L.stride, L.stride, L.pad, L.pad)
+        self.F = self.d.flops
+        xs, ys = (L.N, L.C, L.H, L.W), (L.N, L.K, L.OH, L.OW)
+        z = stgen.normal(4 * seed, int(np.prod(xs))).reshape(xs)
+        g = stgen.normal(4 * seed + 2, int(np.prod(ys))).reshape(ys)
+        u = stgen.uniform(4 * seed + 3, int(np.prod(ys))).reshape(ys)
+        self.w_host = stgen.he_normal((L.K, L.C, L.S, L.R), 4 * seed + 1)
+        # first image of every tensor, for the CPU baseline and for the check of the on-device derivation
+        self.host0 = (z[:CPU_IMAGES].copy(), g[:CPU_IMAGES].copy(), u[:CPU_IMAGES].copy()) if keep_host_image else None
+        self.z = torch.from_numpy(st.pack_activations(z)).to(dev)
+        self.g = torch.from_numpy(st.pack_activations(g)).to(dev)
+        self.u = torch.from_numpy(st.pack_activations(u)).to(dev)
+        del z, g, u
+        self.w = torch.from_numpy(st.pack_filters(self.w_host)).to(dev)
+        self.x = torch.empty(self.z.shape, dtype=torch.float32, device=dev)
+        self.dy = torch.empty(self.g.shape, dtype=torch.float32, device=dev)
+        self.y = torch.empty_like(self.dy)
+        self.dx = torch.empty_like(self.x)
+        self.dw = torch.empty_like(self.w)
+        self.ws = {}
+        for p in (st.ST_PASS_FWD, st.ST_PASS_BWI, st.ST_PASS_BWW):
+            for dense in (False, True):
+                n = st.st_conv_workspace_bytes(self.d, p, dense)
+                self.ws[p, dense] = torch.empty(max(n, 4) // 4, dtype=torch.float32, device=dev) if n else None
+        self.px = self.pdy = None
 
+    def set_level(self, p, stgen):
+        """x = max(0, z - t) and dy = g * (u >= p), computed in fp64 and rounded once to fp32: the same
+        bits as stgen.relu_from_normal / stgen.mask_from_uniform give on the host."""
+        torch = self.torch
+        if p <= 0.0:
+            self.x.copy_(self.z)
+            self.dy.copy_(self.g)
+        else:
+            self.x.copy_(torch.clamp_min(self.z - stgen.relu_threshold(p), 0.0))
+            self.dy.copy_(self.g.to(torch.float32) * (self.u >= p).to(torch.float32))
+        self.px = float((self.x == 0).sum()) / self.x.numel()
+        self.pdy = float((self.dy == 0).sum()) / self.dy.numel()
+
+    def check_derivation(self, p, stgen):
+        """The first image of x and dy on the device against the host generator (bit for bit)."""
+        import numpy as np
+        z0, g0, u0 = self.host0
+        x0 = self.st.pack_activations(stgen.relu_from_normal(z0, p))
+        dy0 = self.st.pack_activations(stgen.mask_from_uniform(g0, u0, p))
+        n0 = x0.shape[0]
+        ok = np.array_equal(self.x[:n0].cpu().numpy().view(np.uint32), x0.view(np.uint32)) and \
+            np.array_equal(self.dy[:n0].cpu().numpy().view(np.uint32), dy0.view(np.uint32))
+        assert ok, f"{self.L.name}: device-derived inputs differ from the host generator at p={p}"
+
+    def run(self, name, dense, stream):
+        st, d = self.st, self.d
+        if name == "fwd":
+            (st.st_conv_fwd_dense if dense else st.st_conv_fwd)(d, self.x, self.w, self.y, self.ws[0, dense], stream)
+        elif name == "bwi":
+            (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(d, self.dy, self.w, self.dx, self.ws[1, dense], stream)
+        else:
+            (st.st_conv_bww_dense if dense else st.st_conv_bww)(d, self.x, self.dy, self.dw, self.ws[2, dense], stream)
+
+
+def single_layer_config(label, layer, seed, st, stgen, torch, dev, stream, iters, sustain_ms, cold=False):
+    """Sparse and dense time of the three passes of one layer on stgen inputs at the layer's own zero
+    fractions; cold = True also times the 1x1 layers over rotating buffer sets larger than the 256 MB
+    last-level cache."""
+    Ld = LayerOnDevice(layer, seed, st, stgen, torch, dev, keep_host_image=False)
+    L = layer
+    # the layer's own zero fractions differ for x and dy
+    t = stgen.relu_threshold(L.p_x) if L.p_x > 0 else None
+    Ld.x.copy_(Ld.z if t is None else torch.clamp_min(Ld.z - t, 0.0))
+    Ld.dy.copy_(Ld.g.to(torch.float32) * (Ld.u >= L.p_dy).to(torch.float32) if L.p_dy > 0 else Ld.g)
+    px = float((Ld.x == 0).sum()) / Ld.x.numel()
+    pdy = float((Ld.dy == 0).sum()) / Ld.dy.numel()
+    out = {"layer": f"{L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S} N={L.N}", "zero_fraction_x": round(px, 4),
+           "zero_fraction_dy": round(pdy, 4), "flops_per_pass": Ld.F}
+    for name, tested in (("fwd", px), ("bwi", pdy), ("bww", px)):
+        s, _ = time_call(lambda: Ld.run(name, False, stream), iters, sustain_ms, stream)
+        dn, _ = time_call(lambda: Ld.run(name, True, stream), iters, sustain_ms, stream)
+        out[name] = {"sparse_ms": round(s, 4), "dense_ms": round(dn, 4), "speedup": round(dn / s, 3),
+                     "effective_tflops": round(Ld.F / s / 1e9, 2)}
+    if cold:
+        # rotate over enough copies of (input, output) that a launch never finds its tensors in the cache
+        per_set = (Ld.x.numel() + Ld.y.numel()) * 4
+        copies = max(2, int(768e6 // per_set) + 1)
+        xs = [Ld.x.clone() for _ in range(copies)]
+        dys = [Ld.dy.clone() for _ in range(copies)]
+        ys = [torch.empty_like(Ld.y) for _ in range(copies)]
+        dxs = [torch.empty_like(Ld.dx) for _ in range(copies)]
+        d = Ld.d
+        for name, dense, fn in (("fwd", False, st.st_conv_fwd), ("fwd", True, st.st_conv_fwd_dense),
+                                ("bwi", False, st.st_conv_bwi), ("bwi", True, st.st_conv_bwi_dense)):
+            state = {"i": 0}
+
+            def call():
+                i = state["i"] = (state["i"] + 1) % copies
+                if name == "fwd":
+                    fn(d, xs[i], Ld.w, ys[i], Ld.ws[0, dense], stream)
+                else:
+                    fn(d, dys[i], Ld.w, dxs[i], Ld.ws[1, dense], stream)
+
+            m, _ = time_call(call, max(iters, 2 * copies), sustain_ms, stream)
+            out[name]["cold_dense_ms" if dense else "cold_sparse_ms"] = round(m, 4)
+        bytes_moved = {"fwd": (Ld.x.numel() + Ld.y.numel() + Ld.w.numel()) * 4,
+                       "bwi": (Ld.dy.numel() + Ld.dx.numel() + Ld.w.numel()) * 4}
+        for name in ("fwd", "bwi"):
+            out[name]["cold_dense_hbm_frac"] = round(bytes_moved[name] / (out[name]["cold_dense_ms"] * 1e-3) / 1e12 / PEAK_HBM_TBS, 3)
+            out[name]["cold_sparse_hbm_frac"] = round(bytes_moved[name] / (out[name]["cold_sparse_ms"] * 1e-3) / 1e12 / PEAK_HBM_TBS, 3)
+        out["cold_buffer_sets"] = copies
+    return out
+
+
+def write_table1(path, st, stgen, torch, dev, stream, sustain_ms=30.0, iters=7):
+    """Every row of the paper's Table 1 at 50 % zeros (N=32; vgg1_2 as in the stack): all entry points."""
     rows = []
-    totals = {}                     # cfg -> [sparse, dense, auto, best] summed over its rows (us)
-
-    def run(cfg, L, px, pdy, group=None):
-        d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, L.stride, L.stride, L.pad, L.pad)
-        x = relu_sparse((L.N, L.C // 16, L.H, L.W, 16), px)
-        dy = masked((L.N, L.K // 16, L.OH, L.OW, 16), pdy)
-        w = torch.randn((L.K // 16, L.C // 16, L.S, L.R, 16, 16), device=dev) * math.sqrt(2.0 / (L.C * L.R * L.S))
-        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
-        zx = float((x == 0).float().mean())
-        zdy = float((dy == 0).float().mean())
-
-        def ws(p, dn):
-            n = st.st_conv_workspace_bytes(d, p, dn)
-            return torch.empty(max(n // 4, 1), device=dev) if n else None
-
-        for name, fs, fd, fa, a, b, o, pi, pa, z in (
-                ("FWD", st.st_conv_fwd, st.st_conv_fwd_dense, st.st_conv_fwd_auto, x, w, y, 0, st.ST_PASS_FWD_AUTO, zx),
-                ("BWI", st.st_conv_bwi, st.st_conv_bwi_dense, st.st_conv_bwi_auto, dy, w, dx, 1, st.ST_PASS_BWI_AUTO, zdy),
-                ("BWW", st.st_conv_bww, st.st_conv_bww_dense, st.st_conv_bww_auto, x, dy, dw, 2, st.ST_PASS_BWW_AUTO, zx)):
-            wss, wsd, wsa = ws(pi, False), ws(pi, True), ws(pa, False)
-            ts = timeit(lambda: fs(d, a, b, o, wss, stream))
-            td = timeit(lambda: fd(d, a, b, o, wsd, stream))
-            ta = timeit(lambda: fa(d, a, b, o, wsa, stream))
+    tot = [0.0, 0.0, 0.0, 0.0]
+    for i, L in enumerate(stgen.table1_layers(32, 0.5, 0.5)):
+        Ld = LayerOnDevice(L, 300 + i, st, stgen, torch, dev, keep_host_image=False)
+        Ld.set_level(0.5, stgen)
+        d = Ld.d
+        wsa = {}
+        for p in (st.ST_PASS_FWD_AUTO, st.ST_PASS_BWI_AUTO, st.ST_PASS_BWW_AUTO, st.ST_PASS_BWW_DY):
+            n = st.st_conv_workspace_bytes(d, p, False)
+            wsa[p] = torch.empty(max(n, 4) // 4, dtype=torch.float32, device=dev) if n else None
+        label = f"{L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S}" + (f"/{L.stride}" if L.stride != 1 else "")
+        for name, auto, a, b, o, pa, z in (("fwd", st.st_conv_fwd_auto, Ld.x, Ld.w, Ld.y, st.ST_PASS_FWD_AUTO, Ld.px),
+                                           ("bwi", st.st_conv_bwi_auto, Ld.dy, Ld.w, Ld.dx, st.ST_PASS_BWI_AUTO, Ld.pdy),
+                                           ("bww", st.st_conv_bww_auto, Ld.x, Ld.dy, Ld.dw, st.ST_PASS_BWW_AUTO, Ld.px)):
+            ts, _ = time_call(lambda: Ld.run(name, False, stream), iters, sustain_ms, stream)
+            td, _ = time_call(lambda: Ld.run(name, True, stream), iters, sustain_ms, stream)
+            ta, _ = time_call(lambda: auto(d, a, b, o, wsa[pa], stream), iters, sustain_ms, stream)
             best = min(ts, td)
-            eff = d.flops / ts / 1e9
-            label = f"{L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S}" + (f"/{L.stride}" if L.stride != 1 else "") + f" N={L.N}"
-            rows.append(f"| {cfg} | {label} | {name} | {z:.2f} | {ts * 1e3:.0f} | "
-                        f"{td * 1e3:.0f} | {eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | "
-                        f"{d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} | {ta * 1e3:.0f} |")
-            if name == "BWW":       # the same tensor with the zero test on dy (st_conv_bww_dy); same dense control
-                wsy = ws(st.ST_PASS_BWW_DY, False)
-                ty = timeit(lambda: st.st_conv_bww_dy(d, a, b, o, wsy, stream))
+            extra = ""
+            if name == "bww":
+                ty, _ = time_call(lambda: st.st_conv_bww_dy(d, Ld.x, Ld.dy, Ld.dw, wsa[st.ST_PASS_BWW_DY], stream),
+                                  iters, sustain_ms, stream)
                 best = min(best, ty)
-                effy = d.flops / ty / 1e9
-                rows.append(f"| {cfg} | {label} | BWW(dy) | {zdy:.2f} | {ty * 1e3:.0f} | {td * 1e3:.0f} | {effy:.1f} | "
-                            f"{effy * (1 - zdy) / PEAK_FP32_VECTOR:.3f} | {d.flops / td / 1e9 / PEAK_FP32_MFMA:.3f} | "
-                            f"{td / ty:.2f} | |")
-            t = totals.setdefault(group or str(cfg), [0.0, 0.0, 0.0, 0.0])
-            for i, v in enumerate((ts, td, ta, best)):
-                t[i] += v * 1e3
-        del x, dy, w, y, dx, dw
-
-    run(3, stgen.RESNET3_2, stgen.RESNET3_2.p_x, stgen.RESNET3_2.p_dy)
-    for L in stgen.BOTTLENECK:
-        run(4, L, L.p_x, L.p_dy)
-    for p in (0.0, 0.3, 0.5, 0.7, 0.9):
-        for L in stgen.vgg16_stack(p):
-            if L.name in ("vgg3_3", "vgg4_3", "vgg5_2", "vgg5_3"):      # same shapes as 3_2, 4_2, 5_1
-                continue
-            run(5, L, p, p, group=f"5 at {p:.0%} zeros")
-    # every row of the paper's Table 1 (stride-2 and the late 1x1 layers included) at 50 % zeros
-    for L in stgen.table1_layers(32, 0.5, 0.5):
-        if L.name == "vgg1_2":
-            L = stgen.Layer(L.name, 16, L.C, L.K, L.H, L.W, L.R, L.S, L.pad, 0.5, 0.5, L.stride)
-        run("T1", L, 0.5, 0.5)
+                extra = f"{ty * 1e3:.0f}"
+            eff = Ld.F / ts / 1e9
+            rows.append(f"| {label} | {name.upper()} | {z:.2f} | {ts * 1e3:.0f} | {td * 1e3:.0f} | {ta * 1e3:.0f} | {extra} | "
+                        f"{eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | {Ld.F / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} |")
+            for k, v in enumerate((ts, td, ta, best)):
+                tot[k] += v * 1e3
+        del Ld
+        torch.cuda.empty_cache()
     with open(path, "w") as f:
-        f.write("# Per-workload timings: `python bench.py --no-cpu --no-sweep --table <this file>` on one MI355X\n\n"
-                "Median of 7 launches (HIP events) per entry point; inputs drawn on the device with the benchmark's\n"
-                "distributions. config 3 = ResNet-34 block, 4 = ResNet-50 bottleneck, 5 = VGG16 stack at 0-90 % zeros,\n"
-                "T1 = every layer of the paper's Table 1 at 50 % zeros. BWW tests x, BWW(dy) tests dy; auto = the\n"
-                "st_conv_*_auto entry point of the pass (form chosen on the device from sampled zero counts).\n\n")
-        f.write("| config | layer | pass | zeros of tested operand | sparse us | dense us | effective TFLOP/s | "
-                "executed / 157.3 (fp32 vector peak) | dense / 157.3 (MFMA peak) | speed-up | auto us |\n")
-        f.write("|---|---|---|---|---|---|---|---|---|---|---|\n")
+        f.write("# Every layer of the paper's Table 1 at 50 % zeros, N=32: `python bench.py --no-cpu --no-sweep --table1 <this file>` on one MI355X\n\n"
+                "Median of 7 launches (HIP events) per entry point after 30 ms of the same launch; stgen inputs (x ReLU-shifted\n"
+                "Gaussian, dy Bernoulli-masked Gaussian, both 50 % zeros). sparse = st_conv_fwd/bwi/bww (BWW tests x),\n"
+                "auto = st_conv_*_auto, BWW(dy) = st_conv_bww_dy.\n\n")
+        f.write("| layer | pass | zeros of tested operand | sparse us | dense us | auto us | BWW(dy) us | effective TFLOP/s | "
+                "executed / 157.3 | dense / 157.3 (MFMA peak) | speed-up |\n|---|---|---|---|---|---|---|---|---|---|---|\n")
         f.write("\n".join(rows) + "\n")
-        f.write("\nSums over the rows of a config (FWD + BWI + BWW of every layer, us): what always calling the\n"
-                "zero-skipping entry points (st_conv_fwd/bwi/bww), always the dense ones, or the self-selecting ones\n"
-                "costs, and the sum of the fastest form per row (BWW(dy) included) as the lower bound of any choice.\n\n")
-        f.write("| config | zero-skipping | dense | auto | fastest form per row | dense / auto |\n|---|---|---|---|---|---|\n")
-        for cfg, t in totals.items():
-            f.write(f"| {cfg} | {t[0]:.0f} | {t[1]:.0f} | {t[2]:.0f} | {t[3]:.0f} | {t[1] / t[2]:.2f} |\n")
+        f.write(f"\nSums over all rows (us): zero-skipping {tot[0]:.0f}, dense {tot[1]:.0f}, auto {tot[2]:.0f}, "
+                f"fastest form per row {tot[3]:.0f}; dense / auto = {tot[1] / tot[2]:.2f}.\n")
 
 
 def main():
@@ -154,16 +233,25 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--sustain-ms", type=float, default=30.0,
-                    help="untimed spell of the launch about to be timed, before every per-pass / table timing")
+    ap.add_argument("--level", type=float, default=0.5, help="zero fraction of x and dy in the timed step")
+    ap.add_argument("--minibatch", type=int, default=32, help="N of the VGG16 stack (32 in the benchmark definition)")
+    ap.add_argument("--sustain-ms", type=float, default=25.0,
+                    help="untimed spell of the launch about to be timed, before every per-pass timing")
     ap.add_argument("--clock-warm-ms", type=float, default=200.0,
                     help="untimed spell of continuous steps before the warm-up steps (sustained clocks)")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the 0-90 %% zero-fraction sweep")
+    ap.add_argument("--no-sweep", action="store_true", help="only the headline zero fraction, no 0-90 %% sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-other", action="store_true", help="skip the single-layer workloads")
     ap.add_argument("--sweep-iters", type=int, default=5)
-    ap.add_argument("--table", metavar="FILE", default=None,
-                    help="also time every other workload of the benchmark definition (ResNet-34 block, ResNet-50 "
-                         "bottleneck, VGG16 stack at 0-90 %% zeros) and write a markdown table to FILE")
+    ap.add_argument("--only-step", action="store_true",
+                    help="run only warm-up and timed steps (the command profiled for profiles/)")
+    ap.add_argument("--profile-layer", metavar="NAME", default=None,
+                    help="run only one layer of the stack (e.g. vgg3_2): --steps launches of the entry point named by "
+                         "--profile-pass at --level; the command rocprofv3 counter runs are made with")
+    ap.add_argument("--profile-pass", choices=("fwd", "bwi", "bww"), default="fwd")
+    ap.add_argument("--profile-dense", action="store_true", help="with --profile-layer: the dense control instead")
+    ap.add_argument("--table1", metavar="FILE", default=None,
+                    help="also time every row of the paper's Table 1 at 50 %% zeros and write a markdown table to FILE")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device-to-device copy kernel (reference for rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -172,6 +260,8 @@ def main():
         print("bench.py: this build runs on one GPU only (one MI355X per box); --gpus must be 1",
               file=sys.stderr)
         sys.exit(2)
+    if args.only_step:
+        args.no_sweep = args.no_cpu = args.no_other = True
 
     import numpy as np
     import torch
@@ -183,55 +273,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     st.load_library()
-
-    L = stgen.VGG3_2_N16
-    d = st.ConvDesc(L.N, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
-    F = d.flops
     stream = torch.cuda.current_stream()
-
-    def upload(x, w, dy):
-        return (torch.from_numpy(st.pack_activations(x)).to(dev),
-                torch.from_numpy(st.pack_filters(w)).to(dev),
-                torch.from_numpy(st.pack_activations(dy)).to(dev))
-
-    x_h, w_h, dy_h = stgen.make_layer_tensors(L, seed=0)
-    px, pdy = stgen.zero_fraction(x_h), stgen.zero_fraction(dy_h)
-    xd, wd, dyd = upload(x_h, w_h, dy_h)
-    y = torch.empty((L.N, L.K // 16, L.OH, L.OW, 16), device=dev)
-    dx = torch.empty((L.N, L.C // 16, L.H, L.W, 16), device=dev)
-    dw = torch.empty((L.K // 16, L.C // 16, L.S, L.R, 16, 16), device=dev)
-
-    def ws_for(p, dense):
-        n = st.st_conv_workspace_bytes(d, p, dense)
-        return torch.empty(max(n, 4) // 4, dtype=torch.float32, device=dev) if n else None
-
-    ws = {(p, dn): ws_for(p, dn) for p in (0, 1, 2) for dn in (False, True)}
-    ws_dy = ws_for(st.ST_PASS_BWW_DY, False)
-    ws_auto = ws_for(st.ST_PASS_BWW_AUTO, False)
-    ws_fauto, ws_bauto = ws_for(st.ST_PASS_FWD_AUTO, False), ws_for(st.ST_PASS_BWI_AUTO, False)
-
-    def run_pass(name, dense, xin=None, dyin=None):
-        xin = xd if xin is None else xin
-        dyin = dyd if dyin is None else dyin
-        if name == "fwd":
-            (st.st_conv_fwd_dense if dense else st.st_conv_fwd)(d, xin, wd, y, ws[0, dense], stream)
-        elif name == "bwi":
-            (st.st_conv_bwi_dense if dense else st.st_conv_bwi)(d, dyin, wd, dx, ws[1, dense], stream)
-        elif name == "bww_dy":          # side measurement: BWW with the zero test on dy (not part of the step)
-            st.st_conv_bww_dy(d, xin, dyin, dw, ws_dy, stream)
-        elif name == "bww_auto":        # side measurement: BWW that samples both operands and picks one
-            st.st_conv_bww_auto(d, xin, dyin, dw, ws_auto, stream)
-        elif name == "fwd_auto":        # side measurements: sparse/dense form picked on the device
-            st.st_conv_fwd_auto(d, xin, wd, y, ws_fauto, stream)
-        elif name == "bwi_auto":
-            st.st_conv_bwi_auto(d, dyin, wd, dx, ws_bauto, stream)
-        else:
-            (st.st_conv_bww_dense if dense else st.st_conv_bww)(d, xin, dyin, dw, ws[2, dense], stream)
-
-    def step():
-        run_pass("fwd", False)
-        run_pass("bwi", False)
-        run_pass("bww", False)
+    t_start = time.perf_counter()
 
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -241,8 +284,44 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.profile_layer:
+        L = [l for l in stgen.vgg16_stack(args.level, args.minibatch) if l.name == args.profile_layer][0]
+        idx = [l.name for l in stgen.vgg16_stack(args.level, args.minibatch)].index(L.name)
+        Ld = LayerOnDevice(L, 10 + idx, st, stgen, torch, dev, keep_host_image=False)
+        Ld.set_level(args.level, stgen)
+        call = lambda: Ld.run(args.profile_pass, args.profile_dense, stream)
+        sustain(call, args.clock_warm_ms)
+        for _ in range(args.warmup):
+            call()
+        med, avg = time_call(call, args.steps, 0.0, stream)
+        tested = Ld.pdy if args.profile_pass == "bwi" else Ld.px
+        print(json.dumps({"layer": L.name, "N": L.N, "pass": args.profile_pass, "dense": args.profile_dense,
+                          "zero_fraction_tested": round(tested, 4), "median_ms": round(med, 4), "avg_ms": round(avg, 4),
+                          "flops": Ld.F, "executed_tflops": round(Ld.F * (1 - (0 if args.profile_dense else tested)) / avg / 1e9, 2)}))
+        return
+
+    # ---- inputs: the twelve layers, draws resident on the device ----
+    stack = [LayerOnDevice(L, 10 + i, st, stgen, torch, dev) for i, L in enumerate(stgen.vgg16_stack(args.level, args.minibatch))]
+    F_stack = sum(Ld.F for Ld in stack)
+    t_inputs = time.perf_counter() - t_start
+
+    def set_level(p):
+        for Ld in stack:
+            Ld.set_level(p, stgen)
+        torch.cuda.synchronize()
+
+    set_level(args.level)
+    for Ld in (stack[0], stack[4], stack[-1]):
+        Ld.check_derivation(args.level, stgen)
+
+    def step():
+        for Ld in stack:
+            Ld.run("fwd", False, stream)
+            Ld.run("bwi", False, stream)
+            Ld.run("bww", False, stream)
+
     # ---- the timed region: W warm-up steps, then exactly K steps ----
-    sustain(step, args.clock_warm_ms, stream)
+    sustain(step, args.clock_warm_ms)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -252,135 +331,138 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value = 3 * F / (ms_per_step * 1e-3) / 1e12
+    value = 3 * F_stack / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-pass timing with events on the launch stream ----
-    def time_pass(name, dense, iters, xin=None, dyin=None, warm=2):
-        sustain(lambda: run_pass(name, dense, xin, dyin), args.sustain_ms, stream)
-        for _ in range(warm):
-            run_pass(name, dense, xin, dyin)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
-        for a, b in evs:
-            a.record(stream)
-            run_pass(name, dense, xin, dyin)
-            b.record(stream)
-        torch.cuda.synchronize()
-        ts = sorted(a.elapsed_time(b) for a, b in evs)
-        return ts[len(ts) // 2], sum(ts) / len(ts)
+    # ---- per layer and pass, at every swept zero fraction: zero-skipping entry point and dense control ----
+    def measure_level(p, iters):
+        set_level(p)
+        rows = []
+        for Ld in stack:
+            row = {"layer": Ld.L.name, "zero_fraction_x": round(Ld.px, 4), "zero_fraction_dy": round(Ld.pdy, 4)}
+            for name in ("fwd", "bwi", "bww"):
+                s_med, s_avg = time_call(lambda: Ld.run(name, False, stream), iters, args.sustain_ms, stream)
+                d_med, _ = time_call(lambda: Ld.run(name, True, stream), iters, args.sustain_ms, stream)
+                row[name] = {"sparse_ms": round(s_med, 4), "dense_ms": round(d_med, 4), "sparse_avg_ms": round(s_avg, 4)}
+            rows.append(row)
+        tot = {}
+        for name in ("fwd", "bwi", "bww"):
+            s = sum(r[name]["sparse_ms"] for r in rows)
+            dn = sum(r[name]["dense_ms"] for r in rows)
+            tot[name] = {"sparse_ms": round(s, 3), "dense_ms": round(dn, 3), "speedup": round(dn / s, 3),
+                         "effective_tflops": round(F_stack / s / 1e9, 1),
+                         "dense_tflops": round(F_stack / dn / 1e9, 1),
+                         "layers_where_sparse_wins": sum(1 for r in rows if r[name]["sparse_ms"] < r[name]["dense_ms"])}
+        s_all = sum(tot[n]["sparse_ms"] for n in tot)
+        d_all = sum(tot[n]["dense_ms"] for n in tot)
+        return {"zero_fraction": p, "stack_sparse_ms": round(s_all, 3), "stack_dense_ms": round(d_all, 3),
+                "stack_speedup": round(d_all / s_all, 3), "effective_tflops": round(3 * F_stack / s_all / 1e9, 1),
+                "passes": tot, "layers": rows}
 
-    tested_p = {"fwd": px, "bwi": pdy, "bww": px}
-    passes = {}
-    for name in ("fwd", "bwi", "bww"):
-        s_med, s_avg = time_pass(name, False, args.steps)
-        d_med, d_avg = time_pass(name, True, args.steps)
-        passes[name] = {
-            "sparse_ms": round(s_med, 4), "dense_ms": round(d_med, 4),
-            "sparse_avg_ms": round(s_avg, 4),
-            "speedup_vs_dense": round(d_med / s_med, 3),
-            "effective_tflops": round(F / (s_med * 1e-3) / 1e12, 2),
-            "executed_tflops": round(F * (1 - tested_p[name]) / (s_med * 1e-3) / 1e12, 2),
-            "dense_tflops": round(F / (d_med * 1e-3) / 1e12, 2),
-            "dense_frac_of_mfma_peak": round(F / (d_med * 1e-3) / 1e12 / PEAK_FP32_MFMA, 3),
-            "tested_zero_fraction": round(tested_p[name], 4),
+    sweep = []
+    headline = None
+    if not args.only_step:
+        levels = (args.level,) if args.no_sweep else tuple(sorted(set(LEVELS) | {args.level}))
+        for p in levels:
+            rec = measure_level(p, args.steps if p == args.level else args.sweep_iters)
+            sweep.append(rec)
+            if p == args.level:
+                headline = rec
+        set_level(args.level)
+
+    # ---- roofline of the kernel that takes most of the step ----
+    # st_conv_fwd and st_conv_bwi both launch fwd_sparse_kernel (BWI on dy with the transposed filter copy), one
+    # launch per call behind a filter-copy launch of 2-6 us that the event time includes (the fraction is that
+    # much pessimistic); together they are 24 of the step's 36 main launches.  Algorithmic work of a launch:
+    # F * (1 - realised zero fraction of the tested operand) flops on the vector ALUs.
+    roofline = None
+    if headline is not None:
+        t_fb = sum(r[n]["sparse_avg_ms"] for r in headline["layers"] for n in ("fwd", "bwi"))
+        t_w = sum(r["bww"]["sparse_avg_ms"] for r in headline["layers"])
+        fl = sum(Ld.F * ((1 - Ld.px) + (1 - Ld.pdy)) for Ld in stack)
+        fl_w = sum(Ld.F * (1 - Ld.px) for Ld in stack)
+        achieved = fl / (t_fb * 1e-3) / 1e12
+        alg_bytes = sum(4 * (2 * Ld.x.numel() + 2 * Ld.y.numel() + 2 * Ld.w.numel()) for Ld in stack)
+        roofline = {
+            "kernel": "fwd_sparse_kernel (every launch of the step: st_conv_fwd and st_conv_bwi of the 12 layers, "
+                      "each including its filter-copy launch)",
+            "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_FP32_VECTOR, 4),
+            "launches_per_step": 24, "avg_launch_ms": round(t_fb / 24, 4),
+            "algorithmic_flops_per_step": fl, "algorithmic_bytes_per_step": alg_bytes,
+            "traffic": None,
+            "share_of_step": round(t_fb / (t_fb + t_w), 3),
+            "bww_sparse_kernel": {"achieved": round(fl_w / (t_w * 1e-3) / 1e12, 2),
+                                  "frac": round(fl_w / (t_w * 1e-3) / 1e12 / PEAK_FP32_VECTOR, 4),
+                                  "avg_launch_ms": round(t_w / 12, 4)},
         }
 
-    dy_med, _ = time_pass("bww_dy", False, args.steps)
-    passes["bww"]["tests_dy_ms"] = round(dy_med, 4)
-    passes["bww"]["tests_dy_zero_fraction"] = round(pdy, 4)
-    passes["bww"]["auto_select_ms"] = round(time_pass("bww_auto", False, args.steps)[0], 4)
-    passes["fwd"]["auto_select_ms"] = round(time_pass("fwd_auto", False, args.steps)[0], 4)
-    passes["bwi"]["auto_select_ms"] = round(time_pass("bwi_auto", False, args.steps)[0], 4)
+    # ---- the single-layer workloads of the benchmark definition ----
+    other = None
+    if not args.no_other:
+        for Ld in stack:
+            Ld.z = Ld.g = Ld.u = None          # the draws are no longer needed
+        torch.cuda.empty_cache()
+        other = {"config2": single_layer_config("config2", stgen.VGG3_2_N16, 0, st, stgen, torch, dev, stream, args.sweep_iters, args.sustain_ms),
+                 "config3": single_layer_config("config3", stgen.RESNET3_2, 0, st, stgen, torch, dev, stream, args.sweep_iters, args.sustain_ms),
+                 "config4": [single_layer_config("config4", L, 0, st, stgen, torch, dev, stream, args.sweep_iters, args.sustain_ms, cold=L.R == 1)
+                             for L in stgen.BOTTLENECK]}
+        c4 = other["config4"]
+        other["config4_sum"] = {n: {"sparse_ms": round(sum(r[n]["sparse_ms"] for r in c4), 4),
+                                    "dense_ms": round(sum(r[n]["dense_ms"] for r in c4), 4)} for n in ("fwd", "bwi", "bww")}
 
-    # side measurement: the same zero fraction of x arranged as whole dead (image, channel) planes
-    xdead_h = stgen.dead_channels(stgen.relu_sparse((L.N, L.C, L.H, L.W), 0.0, 200), px, 201)
-    xdead = torch.from_numpy(st.pack_activations(xdead_h)).to(dev)
-    passes["fwd"]["dead_channel_pattern"] = {
-        "zero_fraction": round(stgen.zero_fraction(xdead_h), 4),
-        "sparse_ms": round(time_pass("fwd", False, args.steps, xdead)[0], 4)}
-    del xdead, xdead_h
-
-    # ---- roofline of the dominant kernel ----
-    # FWD is one launch of the zero-skipping tile kernel (BWI launches the same kernel on dy) behind a
-    # filter-copy launch of about 5 us (1-2 % of the call), so the event time of st_conv_fwd is that
-    # kernel's launch duration plus the copy: the fraction below is the slightly pessimistic one.
-    # Algorithmic work per launch: F * (1 - realised zero fraction) flops on the vector ALUs.
-    dom = max(passes, key=lambda k: passes[k]["sparse_avg_ms"])
-    fwd_avg_ms = passes["fwd"]["sparse_avg_ms"]
-    achieved = F * (1 - px) / (fwd_avg_ms * 1e-3) / 1e12
-    roofline = {
-        "kernel": "fwd_sparse_kernel<3,3,4,8,2,4,4,1,1,0> (st_conv_fwd incl. its 5 us filter copy; st_conv_bwi runs the same kernel on dy)",
-        "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_FP32_VECTOR, 4),
-        "peak_unpacked_fma": PEAK_FP32_FMA, "frac_of_unpacked_fma_peak": round(achieved / PEAK_FP32_FMA, 4),
-        "avg_launch_ms": fwd_avg_ms, "algorithmic_flops_per_launch": F * (1 - px),
-        "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes_per_launch": 4 * (x_h.size + w_h.size + x_h.size * L.K // L.C),
-        "slowest_pass": dom,
-    }
-
-    # ---- sparse-over-dense speedup at 0-90 % zeros ----
-    sweep = []
-    if not args.no_sweep:
-        for p in (0.0, 0.3, 0.5, 0.7, 0.9):
-            xs_h = stgen.relu_sparse((L.N, L.C, L.H, L.W), p, 100)
-            dys_h = stgen.bernoulli_masked((L.N, L.K, L.OH, L.OW), p, 102, 103)
-            xs = torch.from_numpy(st.pack_activations(xs_h)).to(dev)
-            dys = torch.from_numpy(st.pack_activations(dys_h)).to(dev)
-            row = {"zero_fraction": p}
-            for name in ("fwd", "bwi", "bww"):
-                s_med, _ = time_pass(name, False, args.sweep_iters, xs, dys, warm=1)
-                d_med, _ = time_pass(name, True, args.sweep_iters, xs, dys, warm=1)
-                row[name] = {"sparse_ms": round(s_med, 4), "dense_ms": round(d_med, 4),
-                             "speedup": round(d_med / s_med, 3),
-                             "effective_tflops": round(F / (s_med * 1e-3) / 1e12, 2)}
-            row["bww"]["tests_dy_ms"] = round(time_pass("bww_dy", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
-            row["fwd"]["auto_select_ms"] = round(time_pass("fwd_auto", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
-            row["bwi"]["auto_select_ms"] = round(time_pass("bwi_auto", False, args.sweep_iters, xs, dys, warm=1)[0], 4)
-            sweep.append(row)
-            del xs, dys
-
-    # ---- CPU oracle on a bounded sample of the same workload ----
+    # ---- CPU oracle on a bounded sample: the first images of every layer, all three passes ----
     cpu = None
     if not args.no_cpu:
         from oracle import st_ref
-
-        def oracle_step(n_img):
-            g = st_ref.Geom(n_img, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
-            xs_, dys_ = x_h[:n_img], dy_h[:n_img]
+        t_cpu, f_cpu, done = 0.0, 0, 0
+        for Ld in stack:
+            L = Ld.L
+            z0, g0, u0 = Ld.host0
+            n0 = z0.shape[0]
+            x0 = stgen.relu_from_normal(z0, args.level)
+            dy0 = stgen.mask_from_uniform(g0, u0, args.level)
+            g = st_ref.Geom(n0, L.C, L.K, L.H, L.W, L.R, L.S, 1, 1, L.pad, L.pad)
             t = time.perf_counter()
-            st_ref.conv_fwd(g, xs_, w_h)
-            st_ref.conv_bwi(g, dys_, w_h)
-            st_ref.conv_bww(g, xs_, dys_)
-            return time.perf_counter() - t, 3 * g.flops
+            st_ref.conv_fwd(g, x0, Ld.w_host)
+            st_ref.conv_bwi(g, dy0, Ld.w_host)
+            st_ref.conv_bww(g, x0, dy0)
+            t_cpu += time.perf_counter() - t
+            f_cpu += 3 * g.flops
+            done += 1
+            if t_cpu > 45.0:
+                break
+        cpu = {"value": round(f_cpu / t_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": st_ref.threads(), "kind": "oracle",
+               "sample": f"FWD+BWI+BWW of the first {CPU_IMAGES} of {args.minibatch} images of the first {done} of 12 layers, "
+                         f"same tensors as the timed step, {t_cpu:.2f} s of wall time; dense-equivalent flops / time.  "
+                         f"Linear extrapolation to the whole step: {t_cpu * (3 * F_stack) / f_cpu:.0f} s",
+               "extrapolated_step_s": round(t_cpu * (3 * F_stack) / f_cpu, 1)}
 
-        t1img, f1 = oracle_step(1)
-        n_img = int(max(1, min(L.N, 15.0 // max(t1img, 1e-3))))
-        if n_img > 1:
-            tt, ff = oracle_step(n_img)
-        else:
-            tt, ff = t1img, f1
-        cpu = {"value": round(ff / tt / 1e12, 5), "unit": "TFLOP/s", "cores": st_ref.threads(), "kind": "oracle",
-               "sample": f"FWD+BWI+BWW of the first {n_img} of {L.N} images of the same tensors, "
-                         f"{tt:.2f} s of wall time; dense-equivalent flops / time"}
-
-    if args.table:
-        write_config_table(args.table, st, stgen, torch, dev, stream, args.sustain_ms)
+    if args.table1:
+        for Ld in stack:
+            Ld.z = Ld.g = Ld.u = None
+        del stack
+        torch.cuda.empty_cache()
+        write_table1(args.table1, st, stgen, torch, dev, stream, args.sustain_ms)
 
     out = {
-        "metric": "effective conv TFLOP/s (FWD+BWI+BWW, zero-skipping entry points)",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "clock_warm_ms": args.clock_warm_ms,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "vgg3_2-shaped 3x3 conv layer N=16 C=256 K=256 56x56 stride 1 pad 1; "
-                               "x ReLU-shifted Gaussian, dy Bernoulli-masked Gaussian, He-normal filters, seed 0",
-                   "zero_fraction_x": round(px, 4), "zero_fraction_dy": round(pdy, 4),
-                   "flops_per_pass": F},
-        "passes": passes,
+        "metric": "effective conv TFLOP/s (FWD+BWI+BWW, zero-skipping entry points) + speedup vs dense at 0-90% zeros",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "clock_warm_ms": args.clock_warm_ms, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"VGG16 non-initial conv stack (12 layers of Table 1, 3x3 stride 1 pad 1), N={args.minibatch}, "
+                               f"x and dy at {args.level:.0%} zeros (x ReLU-shifted Gaussian, dy Bernoulli-masked Gaussian, "
+                               f"He-normal filters); step = st_conv_fwd + st_conv_bwi + st_conv_bww of every layer",
+                   "zero_fraction": args.level, "flops_per_step": 3 * F_stack, "input_setup_s": round(t_inputs, 1)},
+        "stack_speedup_vs_dense": {f"{r['zero_fraction']:.0%}": r["stack_speedup"] for r in sweep},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "sweep": sweep,
-        "paper_context": "SparseTrain reports 2.19x/1.37x/1.31x/1.51x projected conv-training speedups for "
-                         "VGG16/ResNet-34/ResNet-50/Fixup ResNet-50 on a 6-core Skylake-X CPU (Table 5); "
-                         "other machine, not a target",
+        "other_configs": other,
+        "paper_context": "SparseTrain Table 3 (3x3 layers, 6-core Skylake-X, N=16): FWD/BWI/BWW 1.38/1.40/1.30x over dense "
+                         "direct convolution at 50 % zeros, 2.48/2.45/3.15x at 90 %; projected conv-training speedups "
+                         "2.19x/1.37x/1.31x/1.51x for VGG16/ResNet-34/ResNet-50/Fixup ResNet-50 (Table 5); other machine, "
+                         "not a target",
+        "wall_s": round(time.perf_counter() - t_start, 1),
     }
     print(json.dumps(out))
 
