@@ -34,6 +34,10 @@ PEAK_FP32_VECTOR = 157.3
 PEAK_FP32_MFMA = 157.3
 PEAK_HBM_TBS = 8.0
 LEVELS = (0.0, 0.3, 0.5, 0.7, 0.9)
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (not read in this
+# run: the figure and how it was scaled are in the file named here); None until such a run exists for the kernel
+TRAFFIC_SOURCE = "profiles/fwd_sparse_kernel_hbm_traffic.md"
+TRAFFIC_BYTES_PER_LAUNCH = {}
 CPU_IMAGES = 4          # images per layer the CPU oracle is timed on (of the minibatch of 32): 10-20 s of work
 
 
@@ -250,6 +254,8 @@ def main():
                          "--profile-pass at --level; the command rocprofv3 counter runs are made with")
     ap.add_argument("--profile-pass", choices=("fwd", "bwi", "bww"), default="fwd")
     ap.add_argument("--profile-dense", action="store_true", help="with --profile-layer: the dense control instead")
+    ap.add_argument("--probe-valu", action="store_true",
+                    help="measure the issue rate of bare v_fmac_f32 / MFMA streams (st_probe_issue_rate) and exit")
     ap.add_argument("--table1", metavar="FILE", default=None,
                     help="also time every row of the paper's Table 1 at 50 %% zeros and write a markdown table to FILE")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -283,6 +289,23 @@ def main():
             dst.copy_(src)              # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
+
+    if args.probe_valu:
+        out = torch.empty(256 * 16 * 256, dtype=torch.float32, device=dev)
+        res = {}
+        names = {0: "fmac_value_changes_every_instruction", 1: "fmac_same_value_first_source_x9",
+                 2: "fmac_same_value_second_source_x9", 3: "mfma_f32_32x32x2"}
+        iters = 16000
+        for pattern in (0, 1, 2, 3):
+            for wps in (1, 2, 4):
+                wgs = 256 * wps
+                it = iters if pattern < 3 else iters // 8
+                call = lambda: st.st_probe_issue_rate(pattern, wgs, it, out, stream)
+                med, _ = time_call(call, 7, 300.0 if (pattern, wps) == (0, 1) else 30.0, stream)
+                fl = (2.0 * 64 * 63 if pattern < 3 else 4096.0 * 4) * it * 4 * wgs
+                res[f"{names[pattern]}@{wps}_waves_per_simd"] = round(fl / med / 1e9, 1)
+        print(json.dumps({"probe": "st_probe_issue_rate", "unit": "TFLOP/s", "results": res}))
+        return
 
     if args.profile_layer:
         L = [l for l in stgen.vgg16_stack(args.level, args.minibatch) if l.name == args.profile_layer][0]
@@ -372,28 +395,42 @@ def main():
     # ---- roofline of the kernel that takes most of the step ----
     # st_conv_fwd and st_conv_bwi both launch fwd_sparse_kernel (BWI on dy with the transposed filter copy), one
     # launch per call behind a filter-copy launch of 2-6 us that the event time includes (the fraction is that
-    # much pessimistic); together they are 24 of the step's 36 main launches.  Algorithmic work of a launch:
-    # F * (1 - realised zero fraction of the tested operand) flops on the vector ALUs.
+    # much pessimistic).  The launches of the step are grouped by kernel instance (st_conv_kernel_name); the
+    # instance with the most time is the dominant kernel.  Algorithmic work of a launch: F * (1 - realised zero
+    # fraction of the tested operand) flops on the vector ALUs; bytes: every tensor element once.
     roofline = None
     if headline is not None:
-        t_fb = sum(r[n]["sparse_avg_ms"] for r in headline["layers"] for n in ("fwd", "bwi"))
+        groups = {}
+        for Ld, r in zip(stack, headline["layers"]):
+            for n, pid, tested in (("fwd", st.ST_PASS_FWD, Ld.px), ("bwi", st.ST_PASS_BWI, Ld.pdy)):
+                name = st.st_conv_kernel_name(Ld.d, pid) or "generic"
+                g = groups.setdefault(name, {"ms": 0.0, "flops": 0.0, "bytes": 0, "launches": 0, "calls": []})
+                g["ms"] += r[n]["sparse_avg_ms"]
+                g["flops"] += Ld.F * (1 - tested)
+                g["bytes"] += 4 * (Ld.x.numel() + Ld.y.numel() + Ld.w.numel())
+                g["launches"] += 1
+                g["calls"].append(f"{Ld.L.name}:{n}")
+        t_fb = sum(g["ms"] for g in groups.values())
         t_w = sum(r["bww"]["sparse_avg_ms"] for r in headline["layers"])
-        fl = sum(Ld.F * ((1 - Ld.px) + (1 - Ld.pdy)) for Ld in stack)
         fl_w = sum(Ld.F * (1 - Ld.px) for Ld in stack)
-        achieved = fl / (t_fb * 1e-3) / 1e12
-        alg_bytes = sum(4 * (2 * Ld.x.numel() + 2 * Ld.y.numel() + 2 * Ld.w.numel()) for Ld in stack)
+        name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        fam = sum(g["flops"] for g in groups.values()) / (t_fb * 1e-3) / 1e12
         roofline = {
-            "kernel": "fwd_sparse_kernel (every launch of the step: st_conv_fwd and st_conv_bwi of the 12 layers, "
-                      "each including its filter-copy launch)",
+            "kernel": name, "calls": dom["calls"],
             "bound": "alu", "achieved": round(achieved, 2), "peak": PEAK_FP32_VECTOR, "unit": "TFLOP/s",
             "frac": round(achieved / PEAK_FP32_VECTOR, 4),
-            "launches_per_step": 24, "avg_launch_ms": round(t_fb / 24, 4),
-            "algorithmic_flops_per_step": fl, "algorithmic_bytes_per_step": alg_bytes,
-            "traffic": None,
-            "share_of_step": round(t_fb / (t_fb + t_w), 3),
+            "launches_per_step": dom["launches"], "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
+            "algorithmic_flops_per_launch": dom["flops"] / dom["launches"],
+            "algorithmic_bytes_per_launch": dom["bytes"] // dom["launches"],
+            "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(name), "traffic_source": TRAFFIC_SOURCE if name in TRAFFIC_BYTES_PER_LAUNCH else None,
+            "share_of_step": round(dom["ms"] / (t_fb + t_w), 3),
+            "all_fwd_sparse_kernel_instances": {"achieved": round(fam, 2), "frac": round(fam / PEAK_FP32_VECTOR, 4),
+                                                "share_of_step": round(t_fb / (t_fb + t_w), 3),
+                                                "ms_by_instance": {k: round(v["ms"], 3) for k, v in groups.items()}},
             "bww_sparse_kernel": {"achieved": round(fl_w / (t_w * 1e-3) / 1e12, 2),
                                   "frac": round(fl_w / (t_w * 1e-3) / 1e12 / PEAK_FP32_VECTOR, 4),
-                                  "avg_launch_ms": round(t_w / 12, 4)},
+                                  "avg_launch_ms": round(t_w / 12, 4), "share_of_step": round(t_w / (t_fb + t_w), 3)},
         }
 
     # ---- the single-layer workloads of the benchmark definition ----

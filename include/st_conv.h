@@ -221,6 +221,30 @@ size_t st_conv_workspace_bytes(const st_conv_desc *desc, int pass, int dense);
  */
 int st_conv_sparse_threshold(const st_conv_desc *desc, int pass);
 
+/*
+ * Name of the main kernel st_conv_fwd (pass = ST_PASS_FWD) or st_conv_bwi (ST_PASS_BWI) launches for this
+ * geometry, with its template arguments, as a profiler prints it (e.g. "fwd_sparse_kernel<3, 3, 4, 8, 2,
+ * 4, 4, 1, 1, 0>": filter width, height, tile height, width, channels per lane, wavefronts per SIMD aimed at,
+ * wavefronts sharing a tile, output stride, input spacing, input offset).  For matching profiler output and
+ * timings to calls; host side only, launches nothing.  buf receives at most len bytes including the
+ * terminating NUL.  ST_ERR_UNSUPPORTED for other passes and for geometries the generic kernels serve.
+ */
+st_status st_conv_kernel_name(const st_conv_desc *desc, int pass, char *buf, size_t len);
+
+/*
+ * Measurement aid, not part of the convolution path: runs a bare instruction stream that gives the issue
+ * rate of the vector pipe for the operand patterns of the zero-skipping kernels (Sec. 3.1's broadcast
+ * multiply-add, here v_fmac_f32 with the tested value as one source) or of the matrix pipe.
+ *   pattern 0: 63 independent v_fmac_f32 per iteration, tested-value register changing every instruction
+ *   pattern 1: the same with one tested-value register as FIRST source for nine instructions in a row
+ *   pattern 2: the same with it as SECOND source
+ *   pattern 3: 4 independent v_mfma_f32_32x32x2_f32 per iteration
+ * workgroups of 256 threads (4 wavefronts, one per SIMD), iters iterations each; out (device) receives one
+ * float per thread, workgroups * 256 in all.  flops = 2 * 64 lanes * 63 * iters * 4 * workgroups for patterns
+ * 0-2 and 4096 * 4 * iters * 4 * workgroups for pattern 3.  Asynchronous on the given stream.
+ */
+st_status st_probe_issue_rate(int pattern, int workgroups, int iters, float *out, void *hip_stream);
+
 /* Static, NUL-terminated description of a status value. */
 const char *st_status_str(st_status status);
 

@@ -19,7 +19,7 @@ _LIB_NAME = "libst_conv.so"
 EXPORTS = ("st_conv_fwd", "st_conv_fwd_dense", "st_conv_bwi", "st_conv_bwi_dense", "st_conv_bww",
            "st_conv_bww_dense", "st_conv_bww_dy", "st_conv_bww_auto", "st_conv_fwd_auto", "st_conv_bwi_auto",
            "st_conv_workspace_bytes", "st_conv_sparse_threshold", "st_status_str", "st_conv_version",
-           "st_conv_fwd_static")
+           "st_conv_fwd_static", "st_conv_kernel_name", "st_probe_issue_rate")
 
 
 class StConvError(RuntimeError):
@@ -89,6 +89,10 @@ def load_library():
             fn.restype = ctypes.c_int
         lib.st_conv_fwd_static.argtypes = [ctypes.POINTER(_CDesc), p, p, p, p]
         lib.st_conv_fwd_static.restype = ctypes.c_int
+        lib.st_conv_kernel_name.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int, ctypes.c_char_p, ctypes.c_size_t]
+        lib.st_conv_kernel_name.restype = ctypes.c_int
+        lib.st_probe_issue_rate.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, p, p]
+        lib.st_probe_issue_rate.restype = ctypes.c_int
         lib.st_conv_workspace_bytes.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int, ctypes.c_int]
         lib.st_conv_workspace_bytes.restype = ctypes.c_size_t
         lib.st_conv_sparse_threshold.argtypes = [ctypes.POINTER(_CDesc), ctypes.c_int]
@@ -198,6 +202,23 @@ def st_conv_fwd_static(desc, x, w, y, stream=None, check=True):
     lib = load_library()
     c = desc._c()
     rc = lib.st_conv_fwd_static(ctypes.byref(c), _addr(x), _addr(w), _addr(y), _stream(stream))
+    if check and rc != ST_OK:
+        raise StConvError(rc, st_status_str(rc))
+    return rc
+
+
+def st_conv_kernel_name(desc, conv_pass: int):
+    """Name of the kernel instance st_conv_fwd / st_conv_bwi launches for this geometry, or None where the
+    library has no name to give (other passes, geometries served by the generic kernels)."""
+    c = desc._c()
+    buf = ctypes.create_string_buffer(128)
+    rc = load_library().st_conv_kernel_name(ctypes.byref(c), int(conv_pass), buf, 128)
+    return buf.value.decode() if rc == ST_OK else None
+
+
+def st_probe_issue_rate(pattern: int, workgroups: int, iters: int, out, stream=None, check=True):
+    """Measurement aid: bare v_fmac_f32 / MFMA instruction streams (see include/st_conv.h)."""
+    rc = load_library().st_probe_issue_rate(int(pattern), int(workgroups), int(iters), _addr(out), _stream(stream))
     if check and rc != ST_OK:
         raise StConvError(rc, st_status_str(rc))
     return rc

@@ -14,6 +14,7 @@ namespace st {
 
 constexpr int kBlk = 16;        // channel block of the blocked layouts
 constexpr int kWave = 64;       // CDNA wavefront width
+constexpr size_t kFilterBytesTileMajor = 3u << 20;  // largest filter copy the zero-skipping FWD/BWI keeps L2-resident across channel tiles
 constexpr int kMaxDevices = 64; // per-device set-up state is kept for this many devices of a process
 
 // Geometry of one correlation "act_out[n,ko,oh,ow] = sum act_in[n,ci,oh*P-ph+v,ow*O-pw+u] * f[ko,ci,v,u]".
@@ -36,6 +37,10 @@ struct Geom {
     const unsigned *sel;
     int want;
     unsigned thr;
+    // host side only (st_conv_kernel_name): when set, the launcher of the zero-skipping kernel writes the
+    // name of the kernel instance it would launch here and launches nothing
+    char *describe;
+    int describe_len;
 };
 
 #if defined(__HIPCC__)

@@ -47,6 +47,7 @@ Geom fwd_geom(const st_conv_desc &d, const Dims &o)
     g.R = d.R; g.S = d.S; g.sw = d.stride_w; g.sh = d.stride_h; g.pw = d.pad_w; g.ph = d.pad_h;
     g.uw = 1; g.uh = 1;
     g.sel = nullptr; g.want = 0; g.thr = 0;
+    g.describe = nullptr; g.describe_len = 0;
     return g;
 }
 
@@ -63,6 +64,7 @@ bool bwi_as_fwd(const st_conv_desc &d, const Dims &o, Geom *g)
     g->uw = d.stride_w; g->uh = d.stride_h;
     g->pw = d.R - 1 - d.pad_w; g->ph = d.S - 1 - d.pad_h;
     g->sel = nullptr; g->want = 0; g->thr = 0;
+    g->describe = nullptr; g->describe_len = 0;
     return true;
 }
 
@@ -421,6 +423,25 @@ int st_conv_sparse_threshold(const st_conv_desc *desc, int pass)
     }
     if (!st::fwd_sparse_supported(g) || !st::fwd_dense_supported(g)) return 0;
     return (int)st::fwd_sparse_threshold(g);
+}
+
+st_status st_conv_kernel_name(const st_conv_desc *desc, int pass, char *buf, size_t len)
+{
+    Dims o;
+    st_status rc = validate(desc, &o);
+    if (rc != ST_OK) return rc;
+    if (!buf || len == 0) return ST_ERR_NULL;
+    Geom g = fwd_geom(*desc, o);
+    if (pass == ST_PASS_BWI) {
+        if (!bwi_as_fwd(*desc, o, &g)) return ST_ERR_UNSUPPORTED;
+    } else if (pass != ST_PASS_FWD) {
+        return ST_ERR_UNSUPPORTED;
+    }
+    if (!st::fwd_sparse_supported(g)) return ST_ERR_UNSUPPORTED;
+    buf[0] = 0;
+    g.describe = buf;
+    g.describe_len = (int)(len > 0x7fffffff ? 0x7fffffff : len);
+    return dev(st::launch_fwd_sparse(g, nullptr, nullptr, nullptr, nullptr));
 }
 
 const char *st_status_str(st_status status)

@@ -16,6 +16,7 @@
 //    reused by every non-zero pixel of the tile; they stream from L2 out of a copy of the filters
 //    in wavefront order ([Ko/64][Ci][S][R][64 k], written before every launch), 256 contiguous
 //    bytes per load instruction.
+#include <cstdio>
 #include <type_traits>
 
 #pragma once
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kerne
                                                          const float *__restrict__ f,
                                                          float *__restrict__ out,
                                                          int tiles_w, int tiles_h, int ktiles, int total,
-                                                               int slots_per_xcd)
+                                                               int slots_per_xcd, int kt_major)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
     if (form_deselected(g.sel, g.want, g.thr)) return;          // uniform over the grid, before any barrier
@@ -118,14 +119,18 @@ __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kerne
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int cpart = wave % CS;                    // which share of the input channels
     // Workgroup -> (tile slot, output-channel tile).  Consecutive workgroup ids are dealt round-robin
-    // to the 8 XCDs, each with its own L2; workgroups 8 ids apart run on the same XCD one after the
-    // other.  Every XCD gets a contiguous range of pixel tiles and walks it tile by tile, all
-    // output-channel tiles of a pixel tile first: the input halo shared by those workgroups, and the
-    // halo columns shared with the next pixel tile, are fetched into that L2 once.
+    // to the 8 XCDs, each with its own 4 MB L2; workgroups 8 ids apart run on the same XCD one after the
+    // other.  Every XCD gets a contiguous range of pixel tiles.  With a small filter tensor it walks the
+    // range tile by tile, all output-channel tiles of a pixel tile first: the input halo shared by those
+    // workgroups, and the halo columns shared with the next pixel tile, are fetched into that L2 once.
+    // With filters that would not stay in L2 next to it (kt_major) it walks the whole range once per
+    // output-channel tile instead, so that only one tile's filters (C*S*R*64*KPL values) are live at a
+    // time and the input is what is fetched again (measured on 512->512 @28, N = 32: 885 MB -> 328 MB fetched per launch, same time).
     constexpr int TPW = WAVES / CS;                 // tasks (pixel tiles) per workgroup
     const int xcd = blockIdx.x % 8, seq = blockIdx.x / 8;
-    const int kt = seq % ktiles;
-    const int tile = (xcd * slots_per_xcd + seq / ktiles) * TPW + wave / CS;
+    const int kt = kt_major ? seq / slots_per_xcd : seq % ktiles;
+    const int slot = kt_major ? seq % slots_per_xcd : seq / ktiles;
+    const int tile = (xcd * slots_per_xcd + slot) * TPW + wave / CS;
     const bool valid = tile < total;                // an invalid wavefront only takes part in barriers
     float *lds = lds_all[wave];
 
@@ -466,8 +471,15 @@ hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out,
     const long long slots_per_xcd = (slots + 7) / 8;
     const long long blocks = slots_per_xcd * 8 * ktiles;
     if (tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    // all filters of the layer against the 4 MB of one XCD's L2, which the input stream needs part of
+    const int kt_major = ktiles > 1 && fwd_sparse_filter_bytes(g) > kFilterBytesTileMajor;
+    if (g.describe) {
+        snprintf(g.describe, (size_t)g.describe_len, "fwd_sparse_kernel<%d, %d, %d, %d, %d, %d, %d, %d, %d, %d>", R, S, TH, TW, KPL,
+                 MINW, CS, SD, SU, OFF);
+        return hipSuccess;
+    }
     hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS, SD, SU, OFF>), dim3((unsigned)blocks), dim3(64 * waves), 0, s,
-                       g, in, f, out, tiles_w, tiles_h, ktiles, (int)tiles, (int)slots_per_xcd);
+                       g, in, f, out, tiles_w, tiles_h, ktiles, (int)tiles, (int)slots_per_xcd, kt_major);
     return hipGetLastError();
 }
 

@@ -166,3 +166,29 @@ def test_sparse_threshold_policy():
     assert st.st_conv_sparse_threshold(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), F) == 0
     assert st.st_conv_sparse_threshold(st.ConvDesc(0, 16, 16, 9, 9, 3, 3), F) == -1
     assert st.st_conv_sparse_threshold(vgg, st.ST_PASS_BWW) == -1
+
+
+def test_kernel_name_query():
+    """Host-side: which instance of the zero-skipping FWD / BWI kernel a geometry gets."""
+    vgg = st.ConvDesc(32, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_kernel_name(vgg, st.ST_PASS_FWD) == "fwd_sparse_kernel<3, 3, 4, 8, 2, 4, 4, 1, 1, 0>"
+    # 64 produced channels: one channel per lane on 8x8 tiles; FWD vectorises over K, BWI over C
+    mixed = st.ConvDesc(32, 64, 128, 112, 112, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_kernel_name(mixed, st.ST_PASS_FWD).startswith("fwd_sparse_kernel<3, 3, 4, 8, 2,")
+    assert st.st_conv_kernel_name(mixed, st.ST_PASS_BWI).startswith("fwd_sparse_kernel<3, 3, 8, 8, 1,")
+    # rows of 28 pixels: 7-wide tiles
+    assert st.st_conv_kernel_name(st.ConvDesc(32, 512, 512, 28, 28, 3, 3, 1, 1, 1, 1), st.ST_PASS_FWD) == \
+        "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>"
+    assert st.st_conv_kernel_name(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), st.ST_PASS_FWD) is None   # generic kernel
+    assert st.st_conv_kernel_name(vgg, st.ST_PASS_BWW) is None
+    lib = st.load_library()
+    c = vgg._c()
+    assert lib.st_conv_kernel_name(ctypes.byref(c), 0, None, 16) == 1
+    small = ctypes.create_string_buffer(8)
+    assert lib.st_conv_kernel_name(ctypes.byref(c), 0, small, 8) == 0 and small.value == b"fwd_spa"
+
+
+def test_probe_arguments_are_checked_on_the_host():
+    assert st.st_probe_issue_rate(0, 4, 10, None, check=False) == 1
+    for bad in ((4, 4, 10), (-1, 4, 10), (0, 0, 10), (0, 4, 0), (0, (1 << 20) + 1, 1)):
+        assert st.st_probe_issue_rate(*bad, 256, check=False) == 2

@@ -33,6 +33,17 @@ def test_library_is_the_hip_build():
     assert st.st_conv_version()
 
 
+def test_issue_rate_probe_runs():
+    """The measurement aid of bench.py --probe-valu: every pattern launches and stores its result word
+    (the vector streams start from zeroed registers, so their words are 0; the matrix stream's are finite)."""
+    out = torch.full((8 * 256,), float("nan"), device="cuda")
+    for pattern in range(4):
+        out.fill_(float("nan"))
+        st.st_probe_issue_rate(pattern, 8, 3, out)
+        torch.cuda.synchronize()
+        assert bool((out == 0).all()) if pattern < 3 else bool(torch.isfinite(out).all()), pattern
+
+
 def test_config1_tiny_layer():
     """N=1, C=K=16, 8x8, 3x3 pad 1, x 50 % zeros, dy = g * (FWD output > 0), seed 0."""
     L = stgen.TINY
