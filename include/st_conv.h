@@ -222,10 +222,11 @@ size_t st_conv_workspace_bytes(const st_conv_desc *desc, int pass, int dense);
 int st_conv_sparse_threshold(const st_conv_desc *desc, int pass);
 
 /*
- * Name of the main kernel st_conv_fwd (pass = ST_PASS_FWD) or st_conv_bwi (ST_PASS_BWI) launches for this
- * geometry, with its template arguments, as a profiler prints it (e.g. "fwd_sparse_kernel<3, 3, 4, 8, 2,
- * 4, 4, 1, 1, 0>": filter width, height, tile height, width, channels per lane, wavefronts per SIMD aimed at,
- * wavefronts sharing a tile, output stride, input spacing, input offset).  For matching profiler output and
+ * Name of the main kernel st_conv_fwd (pass = ST_PASS_FWD), st_conv_bwi (ST_PASS_BWI) or st_conv_bww
+ * (ST_PASS_BWW) launches for this geometry, with its template arguments, as a profiler prints it (e.g.
+ * "fwd_sparse_kernel<3, 3, 4, 8, 2, 4, 4, 1, 1, 0>": filter width, height, tile height, width, channels per
+ * lane, wavefronts per SIMD aimed at, wavefronts sharing a tile, output stride, input spacing, input offset;
+ * "bww_sparse_kernel<3, 3, 8, 8, 0>": filter width, height, tile height, width, stride mode).  For matching profiler output and
  * timings to calls; host side only, launches nothing.  buf receives at most len bytes including the
  * terminating NUL.  ST_ERR_UNSUPPORTED for other passes and for geometries the generic kernels serve.
  */

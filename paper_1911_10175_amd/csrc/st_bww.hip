@@ -20,6 +20,7 @@
 //    gradient to the workspace and a second kernel adds the partials in a fixed order
 //    (Sec. 3.4, accumulation of partial results at the end of a sweep), so results are
 //    deterministic without floating-point atomics.
+#include <cstdio>
 #include <cstdlib>
 #include <type_traits>
 
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
             const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
             const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
             if ((mlo | mhi) == 0u) continue;                 // nothing to do for these 4 pixels x 16 channels
+            const unsigned wlo = mlo >> (h * CH), whi = mhi >> (h * CH);     // shifted once per group, not per pixel
             // window of the other operand's halo, this lane's channel
             float dyw[WR][WC];
             const int w0 = Cfg::wrow0(a) * HW + Cfg::wcol0(b0);
@@ -186,13 +188,13 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
                     nhi = xq[(j + 1) * 16 + 1];
                 }
                 const float xs[CH] = {xlo.x, xlo.y, xlo.z, xlo.w, xhi.x, xhi.y, xhi.z, xhi.w};
-                const unsigned mw = (j < 2) ? mlo : mhi;
+                // this wavefront's 8 channels of pixel j sit at constant bit positions of the shifted mask words
+                const unsigned mw = (j < 2) ? wlo : whi;
                 constexpr int sh = (j % 2) * 16;
-                const unsigned bits = (mw >> sh) >> (h * CH) & 0xFFu;     // this wave's 8 channels
-                if (__builtin_expect(bits != 0u, 1)) {
+                if (__builtin_expect((mw & (0xFFu << sh)) != 0u, 1)) {
                     static_for<0, CH>([&](auto CI) __attribute__((always_inline)) {
                         constexpr int ci = decltype(CI)::value;
-                        if (__builtin_expect((bits & (1u << ci)) != 0u, 1)) {
+                        if (__builtin_expect((mw & (1u << (sh + ci))) != 0u, 1)) {
 #pragma unroll
                             for (int v = 0; v < S; ++v)
 #pragma unroll
@@ -761,6 +763,13 @@ hipError_t launch_pw_sparse(const st_conv_desc &d, const st_conv_desc &e, const 
     return reduce_swapped(d, A.splits, ws, dw, s, sel);
 }
 }  // namespace
+
+// name of the kernel instance launch_bww_sparse runs for d (requires bww_fast_supported(d))
+void bww_sparse_kernel_name(const st_conv_desc &d, char *buf, size_t len)
+{
+    if (d.R == 1) snprintf(buf, len, "pw_bww_sparse_kernel<%d>", pw_kpl(d));
+    else snprintf(buf, len, "bww_sparse_kernel<3, 3, %d, %d, %d>", kSparseTH, kSparseTW, bww_s2(d) ? 1 : 0);
+}
 
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                              float *ws, hipStream_t s, const unsigned *sel)

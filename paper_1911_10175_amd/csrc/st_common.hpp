@@ -139,6 +139,7 @@ bool bww_fast_supported(const st_conv_desc &d);
 size_t bww_sparse_workspace(const st_conv_desc &d);
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                              float *ws, hipStream_t s, const unsigned *sel = nullptr);
+void bww_sparse_kernel_name(const st_conv_desc &d, char *buf, size_t len);
 // BWW that tests dy instead of x (operand roles exchanged, transposing final sum)
 bool bww_dy_fast_supported(const st_conv_desc &d);
 size_t bww_sparse_dy_workspace(const st_conv_desc &d);

@@ -431,6 +431,11 @@ st_status st_conv_kernel_name(const st_conv_desc *desc, int pass, char *buf, siz
     st_status rc = validate(desc, &o);
     if (rc != ST_OK) return rc;
     if (!buf || len == 0) return ST_ERR_NULL;
+    if (pass == ST_PASS_BWW) {
+        if (!st::bww_fast_supported(*desc)) return ST_ERR_UNSUPPORTED;
+        st::bww_sparse_kernel_name(*desc, buf, len);
+        return ST_OK;
+    }
     Geom g = fwd_geom(*desc, o);
     if (pass == ST_PASS_BWI) {
         if (!bwi_as_fwd(*desc, o, &g)) return ST_ERR_UNSUPPORTED;
