@@ -171,7 +171,7 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
  * FWD, dy for BWI; about 1024 evenly spaced blocks of 1024 elements), then both forms are enqueued
  * and the one the count does not select returns at once.  The zero-skipping form runs when the
  * sampled zero fraction reaches the break-even point measured for the geometry: 25 % for 3x3
- * layers with K a multiple of 128, 62 % for narrower ones, 80 % / 45 % for FWD / BWI of stride-2
+ * layers with K a multiple of 128, 40 % for narrower ones, 80 % / 45 % for FWD / BWI of stride-2
  * 3x3 layers, 90 % for 1x1 layers with K a multiple of 256, never for other 1x1 layers, always for
  * geometries only the generic kernels cover.  Where the answer is "always" or "never" the call
  * goes straight to that form, without sampling.  The sampled path costs about 15 us over the

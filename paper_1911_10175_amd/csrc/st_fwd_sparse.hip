@@ -31,7 +31,7 @@ bool fwd_sparse_supported(const Geom &g)
 }
 
 // Break-even points measured on the layer shapes of the paper's Table 1: the zero-skipping form needs 20-25 % zeros
-// with 128 output channels per wavefront and about 60 % with 64; the stride-2 FWD tests 2.25 taps
+// with 128 output channels per wavefront and 36-41 % with 64; the stride-2 FWD tests 2.25 taps
 // per element and its BWI is held by the filter stream of small tiles; a 1x1 layer saves K/64
 // multiply-adds per zero.
 unsigned fwd_sparse_threshold(const Geom &g)
@@ -41,7 +41,7 @@ unsigned fwd_sparse_threshold(const Geom &g)
     if (g.sw == 2) return 800;
     if (g.uw == 2) return 450;
     const bool wide = g.Ko % 128 == 0;
-    return wide ? 250 : 620;
+    return wide ? 250 : 400;
 }
 
 namespace {

@@ -149,10 +149,10 @@ def test_sparse_threshold_policy():
     vgg = st.ConvDesc(16, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
     assert st.st_conv_sparse_threshold(vgg, F) == 250 and st.st_conv_sparse_threshold(vgg, B) == 250
     narrow = st.ConvDesc(16, 64, 64, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(narrow, F) == 620
+    assert st.st_conv_sparse_threshold(narrow, F) == 400
     # FWD vectorises over K, BWI over C
     mixed = st.ConvDesc(16, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_sparse_threshold(mixed, F) == 250 and st.st_conv_sparse_threshold(mixed, B) == 620
+    assert st.st_conv_sparse_threshold(mixed, F) == 250 and st.st_conv_sparse_threshold(mixed, B) == 400
     s2 = st.ConvDesc(8, 128, 128, 56, 56, 3, 3, 2, 2, 1, 1)
     assert st.st_conv_sparse_threshold(s2, F) == 800 and st.st_conv_sparse_threshold(s2, B) == 450
     pw = st.ConvDesc(8, 64, 256, 56, 56, 1, 1)
