@@ -148,10 +148,10 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
 /*
  * BWW that picks the tested operand itself, per call: Sec. 5.3 tests the operand with the higher
  * average sparsity, and Sec. 5.4 names the fixed choice a limitation.  A first kernel counts the
- * zeros in a sample of x and of dy (about 1024 evenly spaced blocks of 1024 elements each); then
+ * zeros in a sample of x and of dy (at most 64 evenly spaced blocks of 1024 elements each); then
  * the forms above are enqueued, and those the counts do not select return at once: x is tested
  * unless dy has the strictly larger zero fraction.  Same tensors, same result, no host
- * synchronisation; the cost is the sampling pass (at most 4 MB of x and of dy are read once more)
+ * synchronisation; the cost is the sampling pass (at most 256 KB of x and of dy are read once more)
  * and the empty launches.  Where tiled kernels exist, the dense form (st_conv_bww_dense) is the
  * third candidate: it runs when even the sparser operand has fewer zeros than the measured
  * break-even, 25 % for 3x3 layers (Sec. 5.3 combines the kernels with dense ones layer by layer).
@@ -168,13 +168,13 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
  * FWD and BWI with the choice between the zero-skipping and the dense form made per call on the
  * device.  Sec. 5.3 of the paper combines its kernels with the dense ones layer by layer, from
  * profiled sparsity; here a first kernel counts the zeros in a sample of the tested operand (x for
- * FWD, dy for BWI; about 1024 evenly spaced blocks of 1024 elements), then both forms are enqueued
- * and the one the count does not select returns at once.  The zero-skipping form runs when the
- * sampled zero fraction reaches the break-even point measured for the geometry: 25 % for 3x3
+ * FWD, dy for BWI; at most 64 evenly spaced blocks of 1024 elements) in the same launch that
+ * writes both forms' filter copies, then both forms are enqueued and the one the count does not
+ * select returns at once.  The zero-skipping form runs when the sampled zero fraction reaches the break-even point measured for the geometry: 25 % for 3x3
  * layers with K a multiple of 128, 40 % for narrower ones, 80 % / 45 % for FWD / BWI of stride-2
  * 3x3 layers, 90 % for 1x1 layers with K a multiple of 256, never for other 1x1 layers, always for
  * geometries only the generic kernels cover.  Where the answer is "always" or "never" the call
- * goes straight to that form, without sampling.  The sampled path costs about 15 us over the
+ * goes straight to that form, without sampling.  The sampled path costs one launch more than the
  * direct call; a caller that tracks sparsity itself can compare it with st_conv_sparse_threshold
  * and call the form directly.  Same tensors and layouts as st_conv_fwd / st_conv_bwi, same result
  * to rounding, no host synchronisation.

@@ -31,7 +31,7 @@ struct Geom {
     int uw, uh;          // spacing of the input samples on the grid the taps slide over (1; 2 for the
                          // BWI of a stride-2 layer, whose dy is spread out with zeros in between)
     // sparse/dense choice on the device (st_conv_fwd_auto, st_conv_bwi_auto): when sel is set the
-    // launch does nothing unless the sampled zero fraction of the tested operand, sel[0] / sel[1],
+    // launch does nothing unless the sampled zero fraction of the tested operand (sample_zeros / sample_seen of sel)
     // selects this form: the zero-skipping one (want = 0) from thr per mille upwards, else the
     // dense one (want = 1)
     const unsigned *sel;
@@ -67,23 +67,30 @@ __device__ __forceinline__ void static_for(F &&f)
 // the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
+// Counters written by the sampling workgroups (zero_sample_block): four {zeros, elements} pairs per tensor,
+// x (or the one tested operand) in words 0..7, dy in words 8..15, the dense threshold of st_conv_bww_auto in
+// word 16.
+constexpr int kSelDy = 8, kSelThr = 16;
+__device__ __forceinline__ unsigned sample_zeros(const unsigned *c) { return c[0] + c[2] + c[4] + c[6]; }
+__device__ __forceinline__ unsigned sample_seen(const unsigned *c) { return c[1] + c[3] + c[5] + c[7]; }
+
 __device__ __forceinline__ bool form_deselected(const unsigned *sel, int want, unsigned thr)
 {
     if (!sel) return false;
-    const bool sparse = (unsigned long long)sel[0] * 1000ull >= (unsigned long long)thr * sel[1];
+    const bool sparse = (unsigned long long)sample_zeros(sel) * 1000ull >= (unsigned long long)thr * sample_seen(sel);
     return (sparse ? 0 : 1) != want;
 }
 
-// BWW form choice (st_conv_bww_auto): sel = {zeros of x in the sample, sample size of x, zeros of dy,
-// sample size of dy, dense threshold in per mille}.  dy (want = 1) is tested when its zero fraction
-// is strictly larger, else x (want = 0); when even the sparser operand has fewer zeros than the
-// threshold, the dense form (want = 2) runs instead (threshold 0: never)
+// BWW form choice (st_conv_bww_auto).  dy (want = 1) is tested when its zero fraction is strictly larger,
+// else x (want = 0); when even the sparser operand has fewer zeros than the threshold, the dense form
+// (want = 2) runs instead (threshold 0: never)
 __device__ __forceinline__ bool deselected(const unsigned *sel, int want)
 {
     if (!sel) return false;
-    const bool dy_sparser = (unsigned long long)sel[2] * sel[1] > (unsigned long long)sel[0] * sel[3];
-    const unsigned zb = dy_sparser ? sel[2] : sel[0], nb = dy_sparser ? sel[3] : sel[1];
-    const bool dense = (unsigned long long)zb * 1000ull < (unsigned long long)sel[4] * nb;
+    const unsigned zx = sample_zeros(sel), nx = sample_seen(sel), zy = sample_zeros(sel + kSelDy), ny = sample_seen(sel + kSelDy);
+    const bool dy_sparser = (unsigned long long)zy * nx > (unsigned long long)zx * ny;
+    const unsigned zb = dy_sparser ? zy : zx, nb = dy_sparser ? ny : nx;
+    const bool dense = (unsigned long long)zb * 1000ull < (unsigned long long)sel[kSelThr] * nb;
     return (dense ? 2 : (dy_sparser ? 1 : 0)) != want;
 }
 #endif
@@ -102,10 +109,15 @@ hipError_t launch_generic_bww(const st_conv_desc &d, const float *x, const float
                               bool sparse, hipStream_t s, const unsigned *sel = nullptr);
 hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                                  hipStream_t s, const unsigned *sel = nullptr);
-// counters[0..3] = {zeros, sample size} of x, then of dy (a sample of about 1024 evenly spaced blocks of 1024 elements; dy may be null);
-// counters[4] = dense_thr, the per-mille zero fraction below which st_conv_bww_auto runs its dense form
+// counters = zero counts of a sample of x and (unless null) of dy, at most 64 evenly spaced blocks of 1024 elements
+// each, plus dense_thr, the per-mille zero fraction below which st_conv_bww_auto runs its dense form (layout:
+// kSelDy, kSelThr above)
 hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
                               hipStream_t s, unsigned dense_thr = 0);
+// one launch for st_conv_fwd_auto / st_conv_bwi_auto: sample of the tested operand into sel[0..7], the filter copy
+// of the zero-skipping form into wl and that of the dense form into wd (g = the correlation the kernels run)
+hipError_t launch_auto_prepare(const Geom &g, bool transpose, const float *act, size_t n_act, const float *w,
+                               float *wl, float *wd, unsigned *sel, hipStream_t s);
 // zero fraction (per mille) of the tested operand from which the zero-skipping FWD/BWI form beats the
 // dense one for this geometry (measured; 1001 = never)
 unsigned fwd_sparse_threshold(const Geom &g);

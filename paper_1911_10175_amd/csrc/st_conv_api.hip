@@ -243,9 +243,19 @@ st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float 
         return bwi ? run_bwi(d, act, w, out, left ? p + off : nullptr, left, stream, dense)
                    : run_fwd(d, act, w, out, left ? p + off : nullptr, left, stream, dense);
     }
+    hipError_t e;
+    if (fast_sparse && fast_dense && !st::pw_dense_direct_supported(g)) {
+        // both forms tiled: sample and both filter copies in one launch, then the two main kernels, of which
+        // the one the count does not select returns at once
+        if (st::launch_auto_prepare(g, bwi, act, n_act, w, ws_sparse, ws_dense, sel, s) != hipSuccess) return ST_ERR_DEVICE;
+        g.sel = sel;
+        g.want = 0;
+        if (st::launch_fwd_sparse(g, act, ws_sparse, out, s) != hipSuccess) return ST_ERR_DEVICE;
+        g.want = 1;
+        return dev(st::launch_fwd_dense(g, act, ws_dense, out, s));
+    }
     if (st::launch_zero_sample(act, n_act, nullptr, 0, sel, s) != hipSuccess) return ST_ERR_DEVICE;
     g.sel = sel;
-    hipError_t e;
     // zero-skipping form
     g.want = 0;
     if (fast_sparse) {

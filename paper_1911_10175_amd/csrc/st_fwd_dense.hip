@@ -18,6 +18,7 @@
 #include <cstdlib>
 
 #include "st_common.hpp"
+#include "st_filter_copies.hpp"
 
 namespace st {
 namespace {
@@ -211,41 +212,14 @@ __global__ __launch_bounds__(256, (FwdDenseCfg<R, S, TWD, MODE, PI, PJ>::minw(KQ
     }
 }
 
-// Prologue: filters in MFMA consumption order.  transpose = 0: B[k][c][tap] = w[k][c][tap] (FWD);
-// transpose = 1: the roles of the channel dimensions are swapped and the taps reversed, i.e. the
-// filters of the correlation that computes BWI (SparseTrain Sec. 3.3).  Ko/Ci are the output and
-// reduced channel counts of the correlation that will consume the copy; output channels are
-// padded with zeros to a multiple of 128.
+// Prologue: filters in MFMA consumption order (st_filter_copies.hpp).
 __global__ __launch_bounds__(256) void reformat_filters_kernel(int Ko, int Ci, int S, int R, int transpose,
                                                                const float *__restrict__ w,
                                                                float *__restrict__ wd, size_t total,
                                                                const unsigned *sel, unsigned thr)
 {
     if (form_deselected(sel, 1, thr)) return;       // the copy of a form that will not run is not written
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    const int TAPS = S * R, CiB = Ci / kBlk;
-    size_t t = i;
-    const int j = t % 8; t /= 8;
-    const int l32 = t % 32; t /= 32;
-    const int half = t % 2; t /= 2;
-    const int tap = t % TAPS; t /= TAPS;
-    const int cb = t % CiB;
-    const int kb32 = (int)(t / CiB);
-    const int ko = kb32 * 32 + l32, ci = cb * kBlk + half * 8 + j;
-    float val = 0.f;
-    if (ko < Ko) {
-        const int v = tap / R, u = tap % R;
-        if (!transpose) {
-            // w[K = Ko][C = Ci]: element [ko/16][ci/16][v][u][ci%16][ko%16]
-            val = w[((((size_t)(ko / kBlk) * CiB + ci / kBlk) * S + v) * R + u) * (kBlk * kBlk) + (ci % kBlk) * kBlk + ko % kBlk];
-        } else {
-            // w[K = Ci][C = Ko]: element [ci/16][ko/16][S-1-v][R-1-u][ko%16][ci%16]
-            const int KoB = Ko / kBlk;
-            val = w[((((size_t)(ci / kBlk) * KoB + ko / kBlk) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) + (ko % kBlk) * kBlk + ci % kBlk];
-        }
-    }
-    wd[i] = val;
+    reformat_filters_block(blockIdx.x, Ko, Ci, S, R, transpose, w, wd, total);
 }
 
 // out = part[0] + part[1] + ... (fixed order), float4 at a time, on a capped grid

@@ -3,6 +3,7 @@
 // st_fwd_sparse_impl.hpp; its instances are compiled in the st_fwd_sparse_*.hip files (one per family,
 // so that they build in parallel).
 #include "st_common.hpp"
+#include "st_filter_copies.hpp"
 
 namespace st {
 
@@ -46,12 +47,9 @@ unsigned fwd_sparse_threshold(const Geom &g)
 
 namespace {
 
-// Filters in the order the wavefronts read them: wl[Ko/64][Ci][S][R][64 k] for the correlation g the
-// kernel runs (Ko rounded up to whole groups of 64; the padding is never written and never used).
-// One load instruction of a wavefront then covers 256 contiguous bytes instead of four 64-byte pieces of
-// four cache lines, and the nine taps of a channel sit at immediate offsets of one address.  transpose
-// selects the BWI form (channel roles exchanged, taps reversed; SparseTrain Sec. 3.3): KB x CB are
-// the filter blocks of the LAYER, w its filters in the library layout.
+// Filters in the order the wavefronts read them (st_filter_copies.hpp): one load instruction of a wavefront
+// then covers 256 contiguous bytes instead of four 64-byte pieces of four cache lines, and the nine taps of a
+// channel sit at immediate offsets of one address.  KB x CB are the filter blocks of the LAYER.
 template <bool TRANSPOSE>
 __global__ __launch_bounds__(256) void wave_filters_kernel(int KB, int CB, int S, int R,
                                                            const float *__restrict__ w, float *__restrict__ wl,
@@ -59,24 +57,7 @@ __global__ __launch_bounds__(256) void wave_filters_kernel(int KB, int CB, int S
 {
     if (form_deselected(sel, 0, thr)) return;       // the copy of a form that will not run is not written
     __shared__ float tile[kBlk][kBlk + 1];
-    int t = blockIdx.x;
-    const int u = t % R; t /= R;
-    const int v = t % S; t /= S;
-    const int cb = t % CB;
-    const int kb = t / CB;
-    const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
-    const size_t src = ((((size_t)kb * CB + cb) * S + v) * R + u) * (kBlk * kBlk);        // [ci = a][ki = b]
-    const int SR = S * R;
-    if constexpr (!TRANSPOSE) {
-        const int k = kb * kBlk + b, c = cb * kBlk + a;
-        wl[((size_t)(k / kWave) * (CB * kBlk) + c) * (SR * kWave) + (v * R + u) * kWave + k % kWave] = w[src + a * kBlk + b];
-    } else {
-        tile[a][b] = w[src + a * kBlk + b];
-        __syncthreads();
-        // produced channel = c (fast index b), reduced channel = k (a)
-        const int c = cb * kBlk + b, k = kb * kBlk + a;
-        wl[((size_t)(c / kWave) * (KB * kBlk) + k) * (SR * kWave) + ((S - 1 - v) * R + (R - 1 - u)) * kWave + c % kWave] = tile[b][a];
-    }
+    wave_filters_block<TRANSPOSE>((int)blockIdx.x, KB, CB, S, R, w, wl, tile);
 }
 
 }  // namespace

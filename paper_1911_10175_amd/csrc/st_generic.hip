@@ -8,6 +8,7 @@
 // test in front of it (SparseTrain Sec. 3.1, Alg. 1; Sec. 3.4, Alg. 4), written per output
 // (gather form) so that no two wavefronts update the same element.
 #include "st_common.hpp"
+#include "st_filter_copies.hpp"
 
 namespace st {
 namespace {
@@ -158,75 +159,56 @@ __global__ __launch_bounds__(64) void generic_bww_dy_kernel(st_conv_desc d, int 
     if (active) dw[flt_off(kb, cb, v, u, CB, d.S, d.R) + ci * kBlk + ki] = acc;
 }
 
-struct SampleArgs {
-    const float *t[2];          // x, dy (or one tensor and null)
-    size_t n[2];                // elements
-    unsigned stride[2];         // every stride-th block of 1024 elements is looked at
-    size_t sampled[2];          // number of such blocks
-};
-
-// Zero statistics for the operand choice of BWW (SparseTrain Sec. 5.3 picks the operand with the
-// higher average sparsity): counts the elements equal to zero in a sample of a tensor, one block of
-// 1024 consecutive floats out of every `stride` blocks, and adds {zeros, elements looked at} to
-// out[2 * tensor], out[2 * tensor + 1] with one 64-bit integer atomic per workgroup (order-independent, hence
-// deterministic; the sample is capped at 2^30 elements, so the low word never carries into the high).
-// Atomics to one address are serialised by the memory system at about 25 ns each: a launch uses at
-// most 256 workgroups, and each keeps four loads in flight per thread instead.
-// blockIdx.y selects the tensor: x and dy are sampled by one launch.
-__global__ __launch_bounds__(256) void zero_sample_kernel(SampleArgs a, unsigned *__restrict__ out)
+// Zero statistics for the choice of the form (SparseTrain Sec. 5.3 picks per layer the operand with the higher
+// average sparsity and combines the kernels with dense ones): one workgroup per tensor counts the zeros of a
+// sample: four workgroups per tensor (zero_sample_block) write their {zeros, elements looked at} pairs, word
+// kSelThr receives the dense threshold of st_conv_bww_auto.  Nothing is accumulated, so nothing has to be
+// cleared first and a single launch does it.
+__global__ __launch_bounds__(256) void zero_sample_kernel(const float *__restrict__ x, size_t nx,
+                                                          const float *__restrict__ dy, size_t ny,
+                                                          unsigned *__restrict__ out, unsigned dense_thr)
 {
-    __shared__ unsigned wz[4], wn[4];
-    const int which = blockIdx.y;
-    const float *__restrict__ t = a.t[which];
-    const size_t n = a.n[which], sampled_blocks = a.sampled[which];
-    const unsigned stride = a.stride[which];
-    unsigned zeros = 0, seen = 0;
-    constexpr int UN = 4;
-    for (size_t b0 = blockIdx.x; b0 < sampled_blocks; b0 += (size_t)gridDim.x * UN) {
-        float4 v[UN];
-        bool full[UN];
-#pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const size_t b = b0 + (size_t)i * gridDim.x;
-            const size_t base = b * stride * 1024 + threadIdx.x * 4;
-            full[i] = b < sampled_blocks && base + 3 < n;      // tensors are 64-byte aligned: one 16-byte load
-            v[i] = full[i] ? *reinterpret_cast<const float4 *>(t + base) : make_float4(1.f, 1.f, 1.f, 1.f);
-        }
-#pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const size_t b = b0 + (size_t)i * gridDim.x;
-            const size_t base = b * stride * 1024 + threadIdx.x * 4;
-            if (full[i]) {
-                zeros += (v[i].x == 0.f ? 1u : 0u) + (v[i].y == 0.f ? 1u : 0u) + (v[i].z == 0.f ? 1u : 0u) + (v[i].w == 0.f ? 1u : 0u);
-                seen += 4u;
-            } else if (b < sampled_blocks) {
-                for (int j = 0; j < 4; ++j)
-                    if (base + j < n) {
-                        zeros += t[base + j] == 0.f ? 1u : 0u;
-                        seen += 1u;
-                    }
-            }
-        }
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        zeros += __shfl_down(zeros, off);
-        seen += __shfl_down(seen, off);
-    }
-    if (threadIdx.x % kWave == 0) {
-        wz[threadIdx.x / kWave] = zeros;
-        wn[threadIdx.x / kWave] = seen;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned long long z = wz[0] + wz[1] + wz[2] + wz[3], m = wn[0] + wn[1] + wn[2] + wn[3];
-        if (m) atomicAdd(reinterpret_cast<unsigned long long *>(out + 2 * which), z | (m << 32));    // 8-byte aligned
+    __shared__ unsigned red[8];
+    const int part = blockIdx.x % kSampleParts;
+    if (blockIdx.x < kSampleParts) {
+        zero_sample_block(x, nx, part, out, red);
+        if (blockIdx.x == 0 && threadIdx.x == 0) out[kSelThr] = dense_thr;
+    } else {
+        zero_sample_block(dy, ny, part, out + kSelDy, red);
     }
 }
 
-__global__ void clear_counters_kernel(unsigned *c, unsigned dense_thr)
+// Everything st_conv_fwd_auto / st_conv_bwi_auto need before their two main kernels, in one launch:
+// the first four workgroups sample the tested operand, the next n_wave workgroups write the filter copy of the zero-skipping
+// form, the rest the filter copy of the dense form.  The copies cannot know the sample's verdict (same launch),
+// so both are written: at most 2 x 9.4 MB on the layers of the paper's Table 1, against one launch and its
+// gap saved twice.
+struct PrepareArgs {
+    const float *act;           // tested operand
+    size_t n_act;
+    const float *w;             // the layer's filters, library layout
+    float *wl, *wd;             // the two copies
+    unsigned *sel;              // counters
+    int KB, CB, S, R;           // filter blocks of the layer
+    int Ko, Ci;                 // produced / reduced channels of the correlation the kernels run
+    int transpose;              // BWI
+    unsigned n_wave;            // workgroups of the first copy
+    size_t total_dense;         // elements of the second copy
+};
+
+__global__ __launch_bounds__(256) void auto_prepare_kernel(PrepareArgs a)
 {
-    c[threadIdx.x] = threadIdx.x < 4 ? 0u : dense_thr;
+    __shared__ float tile[kBlk][kBlk + 1];
+    __shared__ unsigned red[8];
+    const unsigned b = blockIdx.x;
+    if (b < kSampleParts) {
+        zero_sample_block(a.act, a.n_act, (int)b, a.sel, red);
+    } else if (b < kSampleParts + a.n_wave) {
+        if (a.transpose) wave_filters_block<true>((int)(b - kSampleParts), a.KB, a.CB, a.S, a.R, a.w, a.wl, tile);
+        else wave_filters_block<false>((int)(b - kSampleParts), a.KB, a.CB, a.S, a.R, a.w, a.wl, tile);
+    } else {
+        reformat_filters_block(b - kSampleParts - a.n_wave, a.Ko, a.Ci, a.S, a.R, a.transpose, a.w, a.wd, a.total_dense);
+    }
 }
 
 inline void out_dims(const st_conv_desc &d, int &OH, int &OW)
@@ -289,25 +271,24 @@ hipError_t launch_generic_bww_dy(const st_conv_desc &d, const float *x, const fl
 hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t ny, unsigned *counters,
                               hipStream_t s, unsigned dense_thr)
 {
-    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(5), 0, s, counters, dense_thr);
-    SampleArgs a;
-    const float *t[2] = {x, dy};
-    const size_t n[2] = {nx, ny};
-    size_t most = 1;
-    for (int i = 0; i < 2; ++i) {
-        a.t[i] = t[i]; a.n[i] = t[i] ? n[i] : 0; a.stride[i] = 1; a.sampled[i] = 0;
-        if (!t[i]) continue;
-        const size_t blocks = (n[i] + 1023) / 1024;
-        // about 1024 blocks spread evenly over the tensor (all of them when there are fewer): 10^6
-        // elements fix a zero fraction to a fraction of a per cent, and the pass stays a few
-        // microseconds whatever the tensor size
-        const size_t stride = (blocks + 1023) / 1024;
-        a.stride[i] = (unsigned)stride;
-        a.sampled[i] = (blocks + stride - 1) / stride;
-        if (a.sampled[i] > most) most = a.sampled[i];
-    }
-    hipLaunchKernelGGL(zero_sample_kernel, dim3((unsigned)(most < 256 ? most : 256), dy ? 2 : 1), dim3(256), 0, s, a,
-                       counters);
+    hipLaunchKernelGGL(zero_sample_kernel, dim3(dy ? 2 * kSampleParts : kSampleParts), dim3(256), 0, s, x, nx, dy, ny, counters,
+                       dense_thr);
+    return hipGetLastError();
+}
+
+hipError_t launch_auto_prepare(const Geom &g, bool transpose, const float *act, size_t n_act, const float *w,
+                               float *wl, float *wd, unsigned *sel, hipStream_t s)
+{
+    PrepareArgs a;
+    a.act = act; a.n_act = n_act; a.w = w; a.wl = wl; a.wd = wd; a.sel = sel;
+    a.KB = (transpose ? g.Ci : g.Ko) / kBlk; a.CB = (transpose ? g.Ko : g.Ci) / kBlk;       // of the layer
+    a.S = g.S; a.R = g.R; a.Ko = g.Ko; a.Ci = g.Ci; a.transpose = transpose ? 1 : 0;
+    const long long n_wave = (long long)a.KB * a.CB * g.S * g.R;
+    a.total_dense = fwd_dense_filter_bytes(g) / sizeof(float);
+    const long long n_dense = (long long)((a.total_dense + 255) / 256);
+    if (n_wave + n_dense + kSampleParts > 0x7fffffffLL) return hipErrorInvalidValue;
+    a.n_wave = (unsigned)n_wave;
+    hipLaunchKernelGGL(auto_prepare_kernel, dim3((unsigned)(kSampleParts + n_wave + n_dense)), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
