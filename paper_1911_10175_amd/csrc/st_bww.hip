@@ -37,10 +37,32 @@ struct BwwArgs {
     int cgroups;               // ceil(C/64)
     // operand selection on the device (st_conv_bww_auto): when sel is set, the launch does nothing
     // unless the sampled zero counts pick the form this launch computes (want: 0 = tests x, 1 = tests dy,
-    // 2 = dense)
+    // 2 = dense; kEitherOperand: a zero-skipping launch that carries the arguments of both of its forms
+    // and computes the one selected)
     const unsigned *sel;
     int want;
+    // the caller exchanged the operands (dy is the tested one): the tested channels are then the
+    // layer's output channels, the lanes its input channels, and the taps come out reversed; the
+    // partial sums are still written in the layer's own filter layout
+    int swapped;
 };
+
+constexpr int kEitherOperand = -1;
+
+// Which of the two argument sets a zero-skipping launch works with.  Returns false when this workgroup
+// has nothing to do: the form it computes was not selected, or it lies outside the selected form's grid.
+__device__ __forceinline__ bool bww_pick(BwwArgs &A, const BwwArgs &B, const float *&tested, const float *&other)
+{
+    if (!A.sel) return true;
+    const int f = selected_form(A.sel);
+    if (A.want != kEitherOperand) return f == A.want;
+    if (f == 2) return false;
+    if (f == 1) {
+        A = B;
+        const float *t = tested; tested = other; other = t;
+    }
+    return (int)blockIdx.x < A.splits && (int)blockIdx.y < ((A.K + 63) / 64) * A.cgroups;
+}
 
 
 // PSTEP = stride of the layer (1 or 2): positions of the halo between neighbouring tile pixels
@@ -83,12 +105,12 @@ struct BwwSparseCfg {
 // the dy halo of the tile (64 output channels)
 // ------------------------------------------------------------------------------------------
 template <int R, int S, int TH, int TW, int MODE = 0>
-__global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
-                                                            const float *__restrict__ dy,
-                                                            float *__restrict__ part)
+__global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *x_in, const float *dy_in,
+                                                            float *__restrict__ part, BwwArgs B)
 {
     using Cfg = BwwSparseCfg<R, S, TH, TW, MODE>;
-    if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
+    const float *x = x_in, *dy = dy_in;                 // tested operand, other operand
+    if (!bww_pick(A, B, x, dy)) return;                 // uniform over the workgroup, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
     constexpr int CH = 8;                 // input channels per wavefront
     constexpr int GP = Cfg::GP;           // pixels per group
@@ -215,12 +237,24 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
 
     if (wave_active && k < A.K) {
         const int kb = k / kBlk, ki = k % kBlk;
-        float *p = part + (size_t)split * A.K * A.C * (S * R) +
-                   ((size_t)kb * CB + cb) * (S * R * kBlk * kBlk) + (h * CH) * kBlk + ki;
+        float *pbase = part + (size_t)split * A.K * A.C * (S * R);
+        if (!A.swapped) {
+            float *p = pbase + ((size_t)kb * CB + cb) * (S * R * kBlk * kBlk) + (h * CH) * kBlk + ki;
 #pragma unroll
-        for (int tp = 0; tp < S * R; ++tp)
+            for (int tp = 0; tp < S * R; ++tp)
 #pragma unroll
-            for (int ci = 0; ci < CH; ++ci) p[tp * (kBlk * kBlk) + ci * kBlk] = acc[ci][tp];
+                for (int ci = 0; ci < CH; ++ci) p[tp * (kBlk * kBlk) + ci * kBlk] = acc[ci][tp];
+        } else {
+            // layer's block [cb: its output channels][kb: its input channels], element [ki][h*8 + ci]: the
+            // lane's 8 tested channels are consecutive, the taps are reversed
+            float *p = pbase + ((size_t)cb * KB + kb) * (S * R * kBlk * kBlk) + ki * kBlk + h * CH;
+#pragma unroll
+            for (int tp = 0; tp < S * R; ++tp) {
+                float4 *q = reinterpret_cast<float4 *>(p + (S * R - 1 - tp) * (kBlk * kBlk));
+                q[0] = make_float4(acc[0][tp], acc[1][tp], acc[2][tp], acc[3][tp]);
+                q[1] = make_float4(acc[4][tp], acc[5][tp], acc[6][tp], acc[7][tp]);
+            }
+        }
     }
 }
 
@@ -433,7 +467,7 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
                                                                float *__restrict__ part)
 {
     constexpr int P = kPwP, CH = 8, GP = 4, KW = 64 * KPL;
-    if (deselected(A.sel, A.want)) return;
+    if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
     __shared__ __attribute__((aligned(16))) float dyT[P * KW];
     __shared__ __attribute__((aligned(16))) float xT[P * 64];
 
@@ -533,9 +567,16 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
         for (int q = 0; q < KPL; ++q) {
             const int k = kt * KW + q * 64 + lane;
             if (k >= A.K) continue;
-            float *p = pbase + ((size_t)(k / kBlk) * CB + cb) * (kBlk * kBlk) + (h * CH) * kBlk + k % kBlk;
+            if (!A.swapped) {
+                float *p = pbase + ((size_t)(k / kBlk) * CB + cb) * (kBlk * kBlk) + (h * CH) * kBlk + k % kBlk;
 #pragma unroll
-            for (int ci = 0; ci < CH; ++ci) p[ci * kBlk] = acc[ci][q];
+                for (int ci = 0; ci < CH; ++ci) p[ci * kBlk] = acc[ci][q];
+            } else {            // exchanged operands: block [cb][k block] of the layer, element [k % 16][h*8 + ci]
+                float4 *p = reinterpret_cast<float4 *>(pbase + ((size_t)cb * KB + k / kBlk) * (kBlk * kBlk) +
+                                                       (k % kBlk) * kBlk + h * CH);
+                p[0] = make_float4(acc[0][q], acc[1][q], acc[2][q], acc[3][q]);
+                p[1] = make_float4(acc[4][q], acc[5][q], acc[6][q], acc[7][q]);
+            }
         }
     }
 }
@@ -547,10 +588,20 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
 // dw may be the first partial itself (every element is read by the thread that later writes it).
 // The grid is capped and workgroups stride over the outputs: a launch whose form was not selected
 // (st_conv_bww_auto) then costs a few hundred workgroup dispatches instead of up to ten thousand.
-__global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, float4 *dw, size_t n4, int splits,
+// sp.f[form] = number of partial sums the form (0 tests x, 1 tests dy, 2 dense) leaves behind; with
+// want = kAnyForm the launch adds up those of whichever form the sampled counts selected, else it
+// belongs to the form `want` and does nothing when another one was selected.
+struct Splits3 { int f[3]; };
+constexpr int kAnyForm = -2;
+__global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, float4 *dw, size_t n4, Splits3 sp,
                                                           const unsigned *sel, int want)
 {
-    if (deselected(sel, want)) return;
+    int form = want < 0 ? 0 : want;
+    if (sel) {
+        form = selected_form(sel);
+        if (want != kAnyForm && form != want) return;
+    }
+    const int splits = form == 0 ? sp.f[0] : form == 1 ? sp.f[1] : sp.f[2];
     __shared__ float4 red[16][64];
     const int o = threadIdx.x % 64, sl = threadIdx.x / 64;
     const size_t nblk = (n4 + 63) / 64;
@@ -576,34 +627,6 @@ __global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, fl
     }
 }
 
-// Run with the operand roles swapped (BWW that tests dy): the summed partials hold
-// dw'[c][k][S-1-v][R-1-u] in the filter layout of a layer with C and K exchanged; this kernel
-// writes dw[k][c][v][u] in the library layout.
-__global__ __launch_bounds__(256) void bww_reduce_swapped_kernel(const float *__restrict__ part,
-                                                                 float *__restrict__ dw, int K, int C, int S,
-                                                                 int R, const unsigned *sel)
-{
-    if (deselected(sel, 1)) return;
-    // a workgroup per 16x16 block (k block, c block, tap) of dw at a time: the source block [ki][ci] is
-    // read row by row (coalesced), then written transposed through LDS
-    __shared__ float tile[kBlk][kBlk + 1];
-    const int nblk = (K / kBlk) * (C / kBlk) * S * R;
-    const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
-    for (int blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
-        int t = blk;
-        const int u = t % R; t /= R;
-        const int v = t % S; t /= S;
-        const int cb = t % (C / kBlk);
-        const int kb = t / (C / kBlk);
-        const size_t src = ((((size_t)cb * (K / kBlk) + kb) * S + (S - 1 - v)) * R + (R - 1 - u)) * (kBlk * kBlk) +
-                           a * kBlk + b;                                   // element [ki = a][ci = b]
-        tile[a][b] = part[src];
-        __syncthreads();
-        dw[((((size_t)kb * (C / kBlk) + cb) * S + v) * R + u) * (kBlk * kBlk) + a * kBlk + b] = tile[b][a];   // [ci = a][ki = b]
-        __syncthreads();
-    }
-}
-
 constexpr size_t kReduceGrid = 512;          // workgroups of 1024 threads: two per compute unit
 constexpr int kSparseTH = 8, kSparseTW = 8;
 constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
@@ -615,7 +638,7 @@ constexpr int kBwwTargetWorkgroups = 512;
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 {
     BwwArgs A;
-    A.sel = nullptr; A.want = 0;
+    A.sel = nullptr; A.want = 0; A.swapped = 0;
     A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W;
     A.OH = (d.H + 2 * d.pad_h - d.S) / d.stride_h + 1;
     A.OW = (d.W + 2 * d.pad_w - d.R) / d.stride_w + 1;
@@ -639,7 +662,7 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw)
 {
     BwwArgs A;
-    A.sel = nullptr; A.want = 0;
+    A.sel = nullptr; A.want = 0; A.swapped = 0;
     A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W; A.OH = d.H; A.OW = d.W; A.pw = 0; A.ph = 0;
     A.tiles_h = A.tiles_w = 1;
     const long long chunks = ((long long)d.N * d.H * d.W + kPwP - 1) / kPwP;
@@ -666,29 +689,10 @@ hipError_t reduce(const st_conv_desc &d, const BwwArgs &A, const float *part, fl
     if (A.splits == 1) return hipSuccess;               // the kernel wrote dw itself
     const size_t n4 = (size_t)d.K * d.C * d.S * d.R / 4;
     const size_t nblk = (n4 + 63) / 64;
+    const int form = A.sel ? A.want : 0;
+    Splits3 sp = {{A.splits, A.splits, A.splits}};
     hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)(nblk < kReduceGrid ? nblk : kReduceGrid)), dim3(1024), 0, s,
-                       reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(dw), n4, A.splits, A.sel,
-                       A.want);
-    return hipGetLastError();
-}
-
-// exchanged roles: the partial sums (filter layout of the layer with C and K exchanged, taps reversed)
-// are first added in place into the first partial, which is then transposed into dw
-hipError_t reduce_swapped(const st_conv_desc &d, int splits, float *part, float *dw, hipStream_t s,
-                          const unsigned *sel)
-{
-    const size_t total = (size_t)d.K * d.C * d.S * d.R;
-    if (splits > 1) {
-        const size_t nblk = (total / 4 + 63) / 64;
-        hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)(nblk < kReduceGrid ? nblk : kReduceGrid)), dim3(1024), 0, s,
-                           reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(part), total / 4, splits,
-                           sel, 1);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    const size_t tblk = total / 256;
-    hipLaunchKernelGGL(bww_reduce_swapped_kernel, dim3((unsigned)(tblk < 4 * kReduceGrid ? tblk : 4 * kReduceGrid)), dim3(256), 0,
-                       s, part, dw, d.K, d.C, d.S, d.R, sel);
+                       reinterpret_cast<const float4 *>(part), reinterpret_cast<float4 *>(dw), n4, sp, A.sel, form);
     return hipGetLastError();
 }
 
@@ -751,16 +755,15 @@ hipError_t launch_pw_sparse(const st_conv_desc &d, const st_conv_desc &e, const 
 {
     const int kpl = pw_kpl(e);
     BwwArgs A = make_args_pw(e, 64 * kpl, 64);
-    A.sel = sel; A.want = swapped ? 1 : 0;
-    float *part = (A.splits == 1 && !swapped) ? dw : ws;
+    A.sel = sel; A.want = swapped ? 1 : 0; A.swapped = swapped ? 1 : 0;
+    float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(e.K, 64 * kpl) * A.cgroups);
     if (kpl == 4) hipLaunchKernelGGL(pw_bww_sparse_kernel<4>, grid, dim3(512), 0, s, A, tested, other, part);
     else if (kpl == 2) hipLaunchKernelGGL(pw_bww_sparse_kernel<2>, grid, dim3(512), 0, s, A, tested, other, part);
     else hipLaunchKernelGGL(pw_bww_sparse_kernel<1>, grid, dim3(512), 0, s, A, tested, other, part);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    if (!swapped) return reduce(d, A, part, dw, s);
-    return reduce_swapped(d, A.splits, ws, dw, s, sel);
+    return reduce(d, A, part, dw, s);
 }
 }  // namespace
 
@@ -779,12 +782,12 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
     if (bww_s2(d)) {
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 1>), grid, dim3(512), 0, s, A, x, dy, part);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 1>), grid, dim3(512), 0, s, A, x, dy, part, A);
         hipError_t err = hipGetLastError();
-        return err != hipSuccess ? err : reduce(d, A, ws, dw, s);
+        return err != hipSuccess ? err : reduce(d, A, part, dw, s);
     }
     if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s, sel);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part, A);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
@@ -822,7 +825,7 @@ size_t bww_sparse_dy_workspace(const st_conv_desc &d)
     if (bww_s2(d)) return (size_t)make_args_s2_dy(d).splits * d.K * d.C * d.S * d.R * sizeof(float);
     const st_conv_desc e = swapped_desc(d);
     const BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
-    return (size_t)A.splits * d.K * d.C * d.S * d.R * sizeof(float);        // always staged, even for one split
+    return (size_t)A.splits * d.K * d.C * d.S * d.R * sizeof(float);
 }
 
 hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
@@ -830,22 +833,55 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
 {
     if (bww_s2(d)) {
         BwwArgs A = make_args_s2_dy(d);
-        A.sel = sel; A.want = 1;
+        A.sel = sel; A.want = 1; A.swapped = 1;
+        float *part = A.splits == 1 ? dw : ws;
         dim3 grid(A.splits, ceil_div(A.K, 64) * A.cgroups);
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, ws);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, part, A);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
-        return reduce_swapped(d, A.splits, ws, dw, s, sel);
+        return reduce(d, A, part, dw, s);
     }
     const st_conv_desc e = swapped_desc(d);
     if (d.R == 1) return launch_pw_sparse(d, e, dy, x, dw, ws, true, s, sel);
     BwwArgs A = make_args(e, kSparseTH, kSparseTW, true);
-    A.sel = sel; A.want = 1;
+    A.sel = sel; A.want = 1; A.swapped = 1;
+    float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, ws);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, part, A);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    return reduce_swapped(d, A.splits, ws, dw, s, sel);
+    return reduce(d, A, part, dw, s);
+}
+
+// st_conv_bww_auto on unit-stride 3x3 layers: one zero-skipping launch that carries the arguments of both
+// operand roles and computes the selected one, the dense launch, and one launch that adds up the partial
+// sums of whichever form ran.  All three forms stage their partial sums in ws (also a single one).
+bool bww_auto_merged_supported(const st_conv_desc &d)
+{
+    return d.R == 3 && d.S == 3 && d.stride_w == 1 && d.stride_h == 1 && bww_fast_supported(d) && bww_dy_fast_supported(d);
+}
+
+hipError_t launch_bww_auto_merged(const st_conv_desc &d, const float *x, const float *dy, float *dw, float *ws,
+                                  hipStream_t s, const unsigned *sel)
+{
+    const st_conv_desc e = swapped_desc(d);
+    BwwArgs A0 = make_args(d, kSparseTH, kSparseTW, true), A1 = make_args(e, kSparseTH, kSparseTW, true);
+    BwwArgs A2 = make_args(d, kDenseTH, kDenseTW, false);
+    A0.sel = A1.sel = A2.sel = sel;
+    A0.want = kEitherOperand; A1.want = kEitherOperand; A1.swapped = 1; A2.want = 2;
+    const int ygroups = ceil_div(d.K, 64) * ceil_div(d.C, 64);      // the same for both operand roles
+    dim3 grid(A0.splits > A1.splits ? A0.splits : A1.splits, ygroups);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A0, x, dy, ws, A1);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), dim3(A2.splits, ygroups), dim3(256), 0, s, A2, x, dy, ws);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    const size_t n4 = (size_t)d.K * d.C * d.S * d.R / 4;
+    const size_t nblk = (n4 + 63) / 64;
+    Splits3 sp = {{A0.splits, A1.splits, A2.splits}};
+    hipLaunchKernelGGL(bww_reduce_kernel, dim3((unsigned)(nblk < kReduceGrid ? nblk : kReduceGrid)), dim3(1024), 0, s,
+                       reinterpret_cast<const float4 *>(ws), reinterpret_cast<float4 *>(dw), n4, sp, sel, kAnyForm);
+    return hipGetLastError();
 }
 
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,

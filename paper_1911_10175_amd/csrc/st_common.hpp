@@ -81,17 +81,21 @@ __device__ __forceinline__ bool form_deselected(const unsigned *sel, int want, u
     return (sparse ? 0 : 1) != want;
 }
 
-// BWW form choice (st_conv_bww_auto).  dy (want = 1) is tested when its zero fraction is strictly larger,
-// else x (want = 0); when even the sparser operand has fewer zeros than the threshold, the dense form
-// (want = 2) runs instead (threshold 0: never)
-__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
+// BWW form choice (st_conv_bww_auto).  dy (form 1) is tested when its zero fraction is strictly larger,
+// else x (form 0); when even the sparser operand has fewer zeros than the threshold, the dense form
+// (form 2) runs instead (threshold 0: never)
+__device__ __forceinline__ int selected_form(const unsigned *sel)
 {
-    if (!sel) return false;
     const unsigned zx = sample_zeros(sel), nx = sample_seen(sel), zy = sample_zeros(sel + kSelDy), ny = sample_seen(sel + kSelDy);
     const bool dy_sparser = (unsigned long long)zy * nx > (unsigned long long)zx * ny;
     const unsigned zb = dy_sparser ? zy : zx, nb = dy_sparser ? ny : nx;
     const bool dense = (unsigned long long)zb * 1000ull < (unsigned long long)sel[kSelThr] * nb;
-    return (dense ? 2 : (dy_sparser ? 1 : 0)) != want;
+    return dense ? 2 : (dy_sparser ? 1 : 0);
+}
+
+__device__ __forceinline__ bool deselected(const unsigned *sel, int want)
+{
+    return sel && selected_form(sel) != want;
 }
 #endif
 
@@ -158,6 +162,11 @@ size_t bww_sparse_dy_workspace(const st_conv_desc &d);
 hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                                 float *ws, hipStream_t s, const unsigned *sel = nullptr);
 size_t bww_dense_workspace(const st_conv_desc &d);
+// st_conv_bww_auto in three launches (zero-skipping with either operand tested, dense, sum of the partials):
+// unit-stride 3x3 layers; ws holds max(splits) * K*C*S*R floats, at least one set
+bool bww_auto_merged_supported(const st_conv_desc &d);
+hipError_t launch_bww_auto_merged(const st_conv_desc &d, const float *x, const float *dy, float *dw, float *ws,
+                                  hipStream_t s, const unsigned *sel);
 hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                             float *ws, hipStream_t s, const unsigned *sel = nullptr);
 // zero fraction (per mille) of the sparser operand below which the dense BWW beats both zero-skipping forms

@@ -121,8 +121,12 @@ size_t workspace_bytes(const st_conv_desc &d, const Dims &o, int pass, bool dens
         // 256 bytes of counters, then the partial sums of whichever form runs
         const size_t a = workspace_bytes(d, o, ST_PASS_BWW, false), b = workspace_bytes(d, o, ST_PASS_BWW_DY, false);
         const size_t c = workspace_bytes(d, o, ST_PASS_BWW, true);
-        const size_t m = a > b ? a : b;
-        return kCounterBytes + (m > c ? m : c);
+        size_t m = a > b ? a : b;
+        if (c > m) m = c;
+        // the three-launch path stages the partial sums of every form, also a single one
+        const size_t one = (size_t)d.K * d.C * d.S * d.R * sizeof(float);
+        if (st::bww_auto_merged_supported(d) && m < one) m = one;
+        return kCounterBytes + m;
     }
     default:
         return 0;
@@ -306,6 +310,7 @@ st_status run_bww_auto(const st_conv_desc *d, const float *x, const float *dy, f
     const unsigned dense_thr = tiled ? st::bww_sparse_threshold(*d) : 0;
     if (dense_thr > 1000) return dev(st::launch_bww_dense(*d, x, dy, dw, part, s));    // never zero-skipping: unsampled
     if (st::launch_zero_sample(x, nx, dy, ny, sel, s, dense_thr) != hipSuccess) return ST_ERR_DEVICE;
+    if (dense_thr != 0 && st::bww_auto_merged_supported(*d)) return dev(st::launch_bww_auto_merged(*d, x, dy, dw, part, s, sel));
     hipError_t e = st::bww_fast_supported(*d) ? st::launch_bww_sparse(*d, x, dy, dw, part, s, sel)
                                               : st::launch_generic_bww(*d, x, dy, dw, true, s, sel);
     if (e != hipSuccess) return ST_ERR_DEVICE;
