@@ -314,8 +314,14 @@ def main():
         return
 
     if args.profile_layer:
-        L = [l for l in stgen.vgg16_stack(args.level, args.minibatch) if l.name == args.profile_layer][0]
-        idx = [l.name for l in stgen.vgg16_stack(args.level, args.minibatch)].index(L.name)
+        # a layer of the timed stack, or any other row of the paper's Table 1 (ResNet-50: 1x1 and stride-2 layers)
+        pool = stgen.vgg16_stack(args.level, args.minibatch)
+        pool += [l for l in stgen.table1_layers(args.minibatch, args.level, args.level) if l.name not in {q.name for q in pool}]
+        names = [l.name for l in pool]
+        if args.profile_layer not in names:
+            sys.exit(f"--profile-layer: unknown layer {args.profile_layer!r}; one of {', '.join(names)}")
+        idx = names.index(args.profile_layer)
+        L = pool[idx]
         Ld = LayerOnDevice(L, 10 + idx, st, stgen, torch, dev, keep_host_image=False)
         Ld.set_level(args.level, stgen)
         call = lambda: Ld.run(args.profile_pass, args.profile_dense, stream)

@@ -98,6 +98,19 @@ def test_small_shapes_all_passes(label, g, px, pdy):
     check_all_passes_full(g, x, w, dy, label)
 
 
+# the dense 1x1 form that keeps the filter matrix in LDS: every instance (64 / 128 / 256 produced channels, channel
+# loops of 4, 8 and 16 blocks, i.e. both prefetch depths), FWD and BWI, with 8268 pixels: 258 whole tiles of 32 and
+# one of 12, spread over 256 workgroups so that some get two tiles and the last ones none
+PW_LDS = [Geom(3, 256, 64, 53, 52, 1, 1), Geom(3, 64, 256, 53, 52, 1, 1), Geom(3, 64, 64, 53, 52, 1, 1),
+          Geom(3, 128, 128, 53, 52, 1, 1), Geom(3, 64, 128, 53, 52, 1, 1), Geom(12, 128, 64, 56, 56, 1, 1)]
+
+
+@pytest.mark.parametrize("g", PW_LDS, ids=[f"{g.C}to{g.K}_n{g.N}" for g in PW_LDS])
+def test_dense_1x1_with_filters_in_lds(g):
+    x, w, dy = synth(g, 0.5, 0.5, seed=29)
+    check_all_passes_full(g, x, w, dy, f"1x1 {g.C}->{g.K}", passes=("fwd", "bwi"), variants=(True,))
+
+
 @pytest.mark.parametrize("p", [0.0, 0.9, 1.0])
 def test_degenerate_sparsity(p):
     """Fully dense, very sparse and all-zero tested operands."""
