@@ -358,84 +358,102 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
 // ------------------------------------------------------------------------------------------
 constexpr int kPwP = 32;            // pixels per staged chunk
 
-// Dense: workgroup = 128 input channels x 128 output channels, wavefront = 64 x 64 (four 32x32 MFMA
-// blocks), so that a staged pixel is used for four times as many MFMAs as in the tap-per-block
-// kernel above; the next chunk is fetched into registers while the current one is multiplied.
+// Dense: workgroup = CW input channels x KW output channels (128 or 64 each), its four wavefronts a 2 x 2
+// grid of (CW/2) x (KW/2) sub-tiles of 32x32 MFMA blocks; the next chunk of P pixels is fetched into registers
+// while the current one is multiplied.  128 x 128 uses a staged pixel for four MFMAs per pair of LDS reads;
+// layers with only 64 channels on a side get the narrower tile (no padded blocks) and chunks of 64 pixels,
+// so that there are as many MFMAs between two barriers.
+template <int CW, int KW, int P>
 __global__ __launch_bounds__(256) void pw_bww_dense_kernel(BwwArgs A, const float *__restrict__ x,
                                                            const float *__restrict__ dy,
                                                            float *__restrict__ part)
 {
     if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
-    constexpr int P = kPwP, CW = 128;                   // channels of either operand per workgroup
+    constexpr int CI = CW / 64, KJ = KW / 64;           // 32x32 blocks per wavefront along c and along k
+    constexpr int NX = P * CW / 4 / 256, ND = P * KW / 4 / 256;      // float4 staging slots per thread
     __shared__ __attribute__((aligned(16))) float xs[P * CW];
-    __shared__ __attribute__((aligned(16))) float ds[P * CW];
+    __shared__ __attribute__((aligned(16))) float ds[P * KW];
 
     // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
     const int l32 = lane % 32, half = lane / 32;
     const int wk = wave % 2, wc = wave / 2;
     const int split = blockIdx.x;
-    const int kt = blockIdx.y / A.cgroups, cg = blockIdx.y % A.cgroups;     // groups of 128 channels here
+    const int kt = blockIdx.y / A.cgroups, cg = blockIdx.y % A.cgroups;     // groups of KW / CW channels here
     const int CB = A.C / kBlk, KB = A.K / kBlk;
     const int HW = A.H * A.W;
-    const long long total_px = (long long)A.N * HW;
 
-    floatx16 acc[2][2];                                 // [c block of 32][k block of 32]
+    floatx16 acc[CI][KJ];                               // [c block of 32][k block of 32]
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < CI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < KJ; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int u0 = (int)((long long)A.units * split / A.splits);
     const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
 
-    // staging slots of this thread: 4 float4 of x and 4 of dy per chunk; slot = (pixel, 4 channels)
-    float4 rx[4], rd[4];
-    auto fetch = [&](int unit) __attribute__((always_inline)) {
+    // staging slots of this thread: slot = (pixel, 4 channels).  (image, pixel) of a chunk's first pixel is
+    // carried from chunk to chunk (one 64-bit division per workgroup instead of one per slot and chunk); a
+    // slot's pixel is that plus its offset, wrapped into the following images.
+    float4 rx[NX], rd[ND];
+    int n0 = (int)((long long)u0 * P / HW), p0 = (int)((long long)u0 * P % HW);
+    auto locate = [&](int pix, int &n, int &p) __attribute__((always_inline)) {
+        n = n0;
+        p = p0 + pix;
+        while (p >= HW) { p -= HW; ++n; }
+        return n < A.N;
+    };
+    auto fetch = [&]() __attribute__((always_inline)) {      // the chunk that starts at (n0, p0)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < NX; ++jj) {
             const int idx = jj * 256 + (int)threadIdx.x;
-            const int pix = idx >> 5, q = idx & 31;                 // 32 float4 = 128 channels per pixel
-            const long long gp = (long long)unit * P + pix;
+            const int pix = idx / (CW / 4), q = idx % (CW / 4);
+            const int cb = cg * (CW / kBlk) + (q >> 2);
+            int n, p;
             rx[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
-            rd[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gp < total_px) {
-                const int n = (int)(gp / HW), p = (int)(gp % HW);
-                const int cb = cg * 8 + (q >> 2), kb = kt * 8 + (q >> 2);
-                if (cb < CB) rx[jj] = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cb) * HW + p) * kBlk + (q & 3) * 4);
-                if (kb < KB) rd[jj] = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
-            }
+            if (locate(pix, n, p) && cb < CB)
+                rx[jj] = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cb) * HW + p) * kBlk + (q & 3) * 4);
         }
+#pragma unroll
+        for (int jj = 0; jj < ND; ++jj) {
+            const int idx = jj * 256 + (int)threadIdx.x;
+            const int pix = idx / (KW / 4), q = idx % (KW / 4);
+            const int kb = kt * (KW / kBlk) + (q >> 2);
+            int n, p;
+            rd[jj] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (locate(pix, n, p) && kb < KB)
+                rd[jj] = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
+        }
+        p0 += P;
+        while (p0 >= HW) { p0 -= HW; ++n0; }
     };
     auto stash = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int idx = jj * 256 + (int)threadIdx.x;
-            *reinterpret_cast<float4 *>(xs + idx * 4) = rx[jj];     // [pixel][128 c]
-            *reinterpret_cast<float4 *>(ds + idx * 4) = rd[jj];     // [pixel][128 k]
-        }
+        for (int jj = 0; jj < NX; ++jj) *reinterpret_cast<float4 *>(xs + (jj * 256 + (int)threadIdx.x) * 4) = rx[jj];     // [pixel][CW c]
+#pragma unroll
+        for (int jj = 0; jj < ND; ++jj) *reinterpret_cast<float4 *>(ds + (jj * 256 + (int)threadIdx.x) * 4) = rd[jj];     // [pixel][KW k]
     };
 
-    if (u0 < u1) fetch(u0);
+    if (u0 < u1) fetch();
     for (int unit = u0; unit < u1; ++unit) {
         __syncthreads();                                // the previous chunk is no longer read
         stash();
         __syncthreads();
-        if (unit + 1 < u1) fetch(unit + 1);             // in flight during the MFMAs below
+        if (unit + 1 < u1) fetch();                     // in flight during the MFMAs below
 #pragma unroll 4
         for (int pp = 0; pp < P / 2; ++pp) {
             const int p = 2 * pp + half;                // A[i = c][kk = half], B[kk = half][j = k]
-            float av[2], bv[2];
+            float av[CI], bv[KJ];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) av[i] = xs[p * CW + wc * 64 + i * 32 + l32];
+            for (int i = 0; i < CI; ++i) av[i] = xs[p * CW + wc * (CW / 2) + i * 32 + l32];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) bv[j] = ds[p * CW + wk * 64 + j * 32 + l32];
+            for (int j = 0; j < KJ; ++j) bv[j] = ds[p * KW + wk * (KW / 2) + j * 32 + l32];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < CI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < KJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
     }
@@ -443,14 +461,14 @@ __global__ __launch_bounds__(256) void pw_bww_dense_kernel(BwwArgs A, const floa
     // D[i = c][j = k]: column = lane % 32, row = 8*(r/4) + 4*(lane/32) + r%4
     float *pbase = part + (size_t)split * A.K * A.C;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int k = kt * CW + wk * 64 + j * 32 + l32;
+    for (int j = 0; j < KJ; ++j) {
+        const int k = kt * KW + wk * (KW / 2) + j * 32 + l32;
         if (k >= A.K) continue;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < CI; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int c = cg * CW + wc * 64 + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                const int c = cg * CW + wc * (CW / 2) + i * 32 + 8 * (r / 4) + 4 * half + (r % 4);
                 if (c < A.C)
                     pbase[((size_t)(k / kBlk) * CB + c / kBlk) * (kBlk * kBlk) + (c % kBlk) * kBlk + k % kBlk] = acc[i][j][r];
             }
@@ -480,7 +498,6 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
     const int cb = cg * 4 + cbl;
     const bool wave_active = cb < CB;
     const int HW = A.H * A.W;
-    const long long total_px = (long long)A.N * HW;
 
     float acc[CH][KPL];
 #pragma unroll
@@ -492,30 +509,37 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
     const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
     const int mpix = lane >> 4, mch = lane & 15;
 
+    // (image, pixel) of the chunk's first pixel, carried from chunk to chunk: one 64-bit division per
+    // workgroup instead of one per staged float4
+    int n0 = (int)((long long)u0 * P / HW), p0 = (int)((long long)u0 * P % HW);
+    auto locate = [&](int pix, int &n, int &p) __attribute__((always_inline)) {
+        n = n0;
+        p = p0 + pix;
+        while (p >= HW) { p -= HW; ++n; }
+        return n < A.N;
+    };
     for (int unit = u0; unit < u1; ++unit) {
         __syncthreads();
         for (int idx = threadIdx.x; idx < P * (KW / 4); idx += 512) {
             const int pix = idx / (KW / 4), q = idx % (KW / 4);
-            const long long gp = (long long)unit * P + pix;
             const int kb = kt * (KW / kBlk) + (q >> 2);
+            int n, p;
             float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gp < total_px && kb < KB) {
-                const int n = (int)(gp / HW), p = (int)(gp % HW);
+            if (locate(pix, n, p) && kb < KB)
                 val = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
-            }
             *reinterpret_cast<float4 *>(dyT + pix * KW + q * 4) = val;
         }
         for (int idx = threadIdx.x; idx < P * 16; idx += 512) {
             const int pix = idx >> 4, q = idx & 15;
-            const long long gp = (long long)unit * P + pix;
             const int cbq = cg * 4 + (q >> 2);
+            int n, p;
             float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gp < total_px && cbq < CB) {
-                const int n = (int)(gp / HW), p = (int)(gp % HW);
+            if (locate(pix, n, p) && cbq < CB)
                 val = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cbq) * HW + p) * kBlk + (q & 3) * 4);
-            }
             *reinterpret_cast<float4 *>(xT + pix * 64 + q * 4) = val;
         }
+        p0 += P;
+        while (p0 >= HW) { p0 -= HW; ++n0; }
         __syncthreads();
         if (!wave_active) continue;
 
@@ -659,21 +683,33 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 }
 
 // 1x1 layers: chunks of kPwP pixels numbered across the minibatch; kw / cw = channels per workgroup
-BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw)
+#ifndef PW_DENSE_WGS
+#define PW_DENSE_WGS 512
+#endif
+BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw, int chunk = kPwP, int target = kBwwTargetWorkgroups)
 {
     BwwArgs A;
     A.sel = nullptr; A.want = 0; A.swapped = 0;
     A.N = d.N; A.C = d.C; A.K = d.K; A.H = d.H; A.W = d.W; A.OH = d.H; A.OW = d.W; A.pw = 0; A.ph = 0;
     A.tiles_h = A.tiles_w = 1;
-    const long long chunks = ((long long)d.N * d.H * d.W + kPwP - 1) / kPwP;
+    const long long chunks = ((long long)d.N * d.H * d.W + chunk - 1) / chunk;
     A.units = (int)chunks;                          // bww_fast_supported bounds N*H*W
     A.cgroups = ceil_div(d.C, cw);
     const int groups = ceil_div(d.K, kw) * A.cgroups;
-    int splits = ceil_div(kBwwTargetWorkgroups, groups);
+    int splits = ceil_div(target, groups);
     if (splits > A.units) splits = A.units;
     if (splits < 1) splits = 1;
     A.splits = splits;
     return A;
+}
+
+// dense 1x1 BWW: channels of one operand per workgroup (128, or 64 for layers with no more than that), and the
+// pixels per staged chunk that go with the tile
+int pw_dense_tile(int channels) { return channels > 64 ? 128 : 64; }
+BwwArgs make_args_pw_dense(const st_conv_desc &d)
+{
+    const int cw = pw_dense_tile(d.C), kw = pw_dense_tile(d.K);
+    return make_args_pw(d, kw, cw, cw == 128 && kw == 128 ? 32 : 64, PW_DENSE_WGS);
 }
 
 int pw_kpl(const st_conv_desc &d) { return d.K % 256 == 0 ? 4 : (d.K % 128 == 0 ? 2 : 1); }
@@ -742,7 +778,7 @@ size_t bww_sparse_workspace(const st_conv_desc &d)
 
 size_t bww_dense_workspace(const st_conv_desc &d)
 {
-    if (d.R == 1 && d.S == 1) return partial_bytes(d, make_args_pw(d, 128, 128));
+    if (d.R == 1 && d.S == 1) return partial_bytes(d, make_args_pw_dense(d));
     if (bww_s2(d)) return partial_bytes(d, make_args(d, kS2TH, kS2TW, false));
     return partial_bytes(d, make_args(d, kDenseTH, kDenseTW, false));
 }
@@ -897,10 +933,15 @@ hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *
         return err != hipSuccess ? err : reduce(d, A2, ws, dw, s);
     }
     if (d.R == 1) {
-        BwwArgs A1 = make_args_pw(d, 128, 128);
+        BwwArgs A1 = make_args_pw_dense(d);
         A1.sel = sel; A1.want = 2;
-        dim3 grid1(A1.splits, ceil_div(d.K, 128) * A1.cgroups);
-        hipLaunchKernelGGL(pw_bww_dense_kernel, grid1, dim3(256), 0, s, A1, x, dy, A1.splits == 1 ? dw : ws);
+        const int cw = pw_dense_tile(d.C), kw = pw_dense_tile(d.K);
+        dim3 grid1(A1.splits, ceil_div(d.K, kw) * A1.cgroups);
+        float *part1 = A1.splits == 1 ? dw : ws;
+        if (cw == 128 && kw == 128) hipLaunchKernelGGL((pw_bww_dense_kernel<128, 128, 32>), grid1, dim3(256), 0, s, A1, x, dy, part1);
+        else if (cw == 128) hipLaunchKernelGGL((pw_bww_dense_kernel<128, 64, 64>), grid1, dim3(256), 0, s, A1, x, dy, part1);
+        else if (kw == 128) hipLaunchKernelGGL((pw_bww_dense_kernel<64, 128, 64>), grid1, dim3(256), 0, s, A1, x, dy, part1);
+        else hipLaunchKernelGGL((pw_bww_dense_kernel<64, 64, 64>), grid1, dim3(256), 0, s, A1, x, dy, part1);
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A1, ws, dw, s);
     }
