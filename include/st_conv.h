@@ -156,7 +156,7 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
  * third candidate: it runs when even the sparser operand has fewer zeros than the measured
  * break-even, 25 % for 3x3 layers (Sec. 5.3 combines the kernels with dense ones layer by layer).
  * Two kinds of layer are decided without sampling: 1x1 layers, where a zero saves too few
- * multiply-adds to beat the matrix cores below about 90 % zeros, go straight to the dense form;
+ * multiply-adds to beat the matrix cores at any zero fraction measured (up to 95 %), go straight to the dense form;
  * stride-2 3x3 layers always test dy (x has four times the elements and each feeds fewer taps,
  * Sec. 3.3, so that form is the faster one at any sparsity).
  * Workspace: st_conv_workspace_bytes(desc, ST_PASS_BWW_AUTO, 0).
@@ -170,12 +170,13 @@ st_status st_conv_bww_auto(const st_conv_desc *desc, const float *x, const float
  * profiled sparsity; here a first kernel counts the zeros in a sample of the tested operand (x for
  * FWD, dy for BWI; at most 64 evenly spaced blocks of 1024 elements) in the same launch that
  * writes both forms' filter copies, then both forms are enqueued and the one the count does not
- * select returns at once.  The zero-skipping form runs when the sampled zero fraction reaches the break-even point measured for the geometry: 25 % for 3x3
- * layers with K a multiple of 128, 40 % for narrower ones, 80 % / 45 % for FWD / BWI of stride-2
- * 3x3 layers, 90 % for 1x1 layers with K a multiple of 256, never for other 1x1 layers, always for
- * geometries only the generic kernels cover.  Where the answer is "always" or "never" the call
- * goes straight to that form, without sampling.  The sampled path costs one launch more than the
- * direct call; a caller that tracks sparsity itself can compare it with st_conv_sparse_threshold
+ * select returns at once.  The zero-skipping form runs when the sampled zero fraction reaches the
+ * break-even point measured for the geometry: 25 % for 3x3 layers with K a multiple of 128, 40 %
+ * for narrower ones, 80 % / 45 % for FWD / BWI of stride-2 3x3 layers, never for 1x1 layers
+ * (measured up to 95 % zeros), always for geometries only the generic kernels cover.  Where the answer is "always" or "never" the call
+ * goes straight to that form, without sampling.  On unit-stride 3x3 layers of the usual sizes one
+ * main kernel holds both forms and runs the selected one, so the sampled path has as many launches
+ * as the direct call (st_conv_kernel_name tells); elsewhere it costs one launch more; a caller that tracks sparsity itself can compare it with st_conv_sparse_threshold
  * and call the form directly.  Same tensors and layouts as st_conv_fwd / st_conv_bwi, same result
  * to rounding, no host synchronisation.
  * Workspace: st_conv_workspace_bytes(desc, ST_PASS_FWD_AUTO or ST_PASS_BWI_AUTO, 0).
@@ -226,9 +227,14 @@ int st_conv_sparse_threshold(const st_conv_desc *desc, int pass);
  * (ST_PASS_BWW) launches for this geometry, with its template arguments, as a profiler prints it (e.g.
  * "fwd_sparse_kernel<3, 3, 4, 8, 2, 4, 4, 1, 1, 0>": filter width, height, tile height, width, channels per
  * lane, wavefronts per SIMD aimed at, wavefronts sharing a tile, output stride, input spacing, input offset;
- * "bww_sparse_kernel<3, 3, 8, 8, 0>": filter width, height, tile height, width, stride mode).  For matching profiler output and
- * timings to calls; host side only, launches nothing.  buf receives at most len bytes including the
- * terminating NUL.  ST_ERR_UNSUPPORTED for other passes and for geometries the generic kernels serve.
+ * "bww_sparse_kernel<3, 3, 8, 8, 0>": filter width, height, tile height, width, stride mode).
+ * With pass = ST_PASS_FWD_AUTO or ST_PASS_BWI_AUTO: the single main kernel of st_conv_fwd_auto /
+ * st_conv_bwi_auto that holds both forms ("fwd_auto_kernel<4, 8, 2, 4, 4, 8>": tile height, width,
+ * channels per lane and wavefronts per tile of the zero-skipping form, column blocks and tile width of
+ * the dense one), ST_ERR_UNSUPPORTED where the two forms are launched separately.  For matching
+ * profiler output and timings to calls; host side only, launches nothing.  buf receives at most len
+ * bytes including the terminating NUL.  ST_ERR_UNSUPPORTED for other passes and for geometries the
+ * generic kernels serve.
  */
 st_status st_conv_kernel_name(const st_conv_desc *desc, int pass, char *buf, size_t len);
 

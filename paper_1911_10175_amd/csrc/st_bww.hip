@@ -955,10 +955,10 @@ hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *
     return reduce(d, A, part, dw, s);
 }
 
-// Measured on the layer shapes of the paper's Table 1: the 3x3 zero-skipping forms pass the dense one at 20-25 % zeros;
-// a 1x1 layer saves at most K/64 (or C/64) multiply-adds per zero and stays behind the matrix cores up
-// to about 90 % zeros, and sampling two tensors costs a quarter of such a short launch: never (1001).  (Stride-2 layers never get here: their dy-testing form beats the dense one
-// even without zeros.)
+// Measured on the layer shapes of the paper's Table 1: the 3x3 zero-skipping forms pass the dense one at
+// 20-25 % zeros; a 1x1 layer saves at most K/64 (or C/64) multiply-adds per zero and stays behind the
+// matrix cores at every zero fraction measured (up to 95 %): never (1001).  (Stride-2 layers never get
+// here: their dy-testing form beats the dense one even without zeros.)
 unsigned bww_sparse_threshold(const st_conv_desc &d)
 {
     if (!bww_fast_supported(d)) return 0;           // generic kernels: the test only ever removes work

@@ -122,6 +122,11 @@ hipError_t launch_zero_sample(const float *x, size_t nx, const float *dy, size_t
 // of the zero-skipping form into wl and that of the dense form into wd (g = the correlation the kernels run)
 hipError_t launch_auto_prepare(const Geom &g, bool transpose, const float *act, size_t n_act, const float *w,
                                float *wl, float *wd, unsigned *sel, hipStream_t s);
+// one main launch that runs whichever of the two forms the sample in g.sel selects (unit-stride 3x3 layers
+// whose two forms both run in workgroups of four wavefronts); wl / wd = the two filter copies
+bool fwd_auto_combined_supported(const Geom &g);
+hipError_t launch_fwd_auto_combined(const Geom &g, const float *in, const float *wl, const float *wd, float *out, hipStream_t s);
+void fwd_auto_kernel_name(const Geom &g, char *buf, size_t len);      // requires fwd_auto_combined_supported(g)
 // zero fraction (per mille) of the tested operand from which the zero-skipping FWD/BWI form beats the
 // dense one for this geometry (measured; 1001 = never)
 unsigned fwd_sparse_threshold(const Geom &g);

@@ -249,11 +249,13 @@ st_status run_fwd_bwi_auto(const st_conv_desc *d, const float *act, const float 
     }
     hipError_t e;
     if (fast_sparse && fast_dense && !st::pw_dense_direct_supported(g)) {
-        // both forms tiled: sample and both filter copies in one launch, then the two main kernels, of which
-        // the one the count does not select returns at once
+        // both forms tiled: sample and both filter copies in one launch, then one main kernel that holds both
+        // forms, or, for the shapes that have none, the two main kernels, of which the one the count does not
+        // select returns at once
         if (st::launch_auto_prepare(g, bwi, act, n_act, w, ws_sparse, ws_dense, sel, s) != hipSuccess) return ST_ERR_DEVICE;
         g.sel = sel;
         g.want = 0;
+        if (st::fwd_auto_combined_supported(g)) return dev(st::launch_fwd_auto_combined(g, act, ws_sparse, ws_dense, out, s));
         if (st::launch_fwd_sparse(g, act, ws_sparse, out, s) != hipSuccess) return ST_ERR_DEVICE;
         g.want = 1;
         return dev(st::launch_fwd_dense(g, act, ws_dense, out, s));
@@ -452,10 +454,16 @@ st_status st_conv_kernel_name(const st_conv_desc *desc, int pass, char *buf, siz
         return ST_OK;
     }
     Geom g = fwd_geom(*desc, o);
-    if (pass == ST_PASS_BWI) {
+    if (pass == ST_PASS_BWI || pass == ST_PASS_BWI_AUTO) {
         if (!bwi_as_fwd(*desc, o, &g)) return ST_ERR_UNSUPPORTED;
-    } else if (pass != ST_PASS_FWD) {
+    } else if (pass != ST_PASS_FWD && pass != ST_PASS_FWD_AUTO) {
         return ST_ERR_UNSUPPORTED;
+    }
+    if (pass == ST_PASS_FWD_AUTO || pass == ST_PASS_BWI_AUTO) {
+        // the single main kernel that holds both forms, where one exists for the geometry
+        if (!st::fwd_auto_combined_supported(g)) return ST_ERR_UNSUPPORTED;
+        st::fwd_auto_kernel_name(g, buf, len);
+        return ST_OK;
     }
     if (!st::fwd_sparse_supported(g)) return ST_ERR_UNSUPPORTED;
     buf[0] = 0;

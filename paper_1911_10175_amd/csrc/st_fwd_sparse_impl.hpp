@@ -89,15 +89,17 @@ struct FwdSparseCfg {
 // (36 multiply-adds per interior element) were measured and are no faster than two on 32 pixels: the
 // filter registers then serve half as many pixels and the 19 TB/s of filter loads this takes at 50 %
 // zeros is more than half of what the L1 caches deliver.
-template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD = 1, int SU = 1, int OFF = 0>
-__global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
-                                                         const float *__restrict__ f,
-                                                         float *__restrict__ out,
-                                                         int tiles_w, int tiles_h, int ktiles, int total,
-                                                               int slots_per_xcd, int kt_major)
+// lds_base: WAVES staging regions of kBlk * PST floats (fwd_sparse_lds_floats), 16-byte aligned.  Every
+// thread of the workgroup makes the call (the body contains barriers when CS > 1).
+template <int R, int S, int TH, int TW, int KPL, int CS, int SD = 1, int SU = 1, int OFF = 0>
+constexpr int fwd_sparse_lds_floats() { return (CS > 4 ? CS : 4) * kBlk * FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>::PST; }
+
+template <int R, int S, int TH, int TW, int KPL, int CS, int SD = 1, int SU = 1, int OFF = 0>
+__device__ __forceinline__ void fwd_sparse_body(const Geom &g, const float *__restrict__ in, const float *__restrict__ f,
+                                                float *__restrict__ out, int tiles_w, int tiles_h, int ktiles, int total,
+                                                int slots_per_xcd, int kt_major, float *lds_base)
 {
     using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
-    if (form_deselected(g.sel, g.want, g.thr)) return;          // uniform over the grid, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, NXV = Cfg::NXV, PST = Cfg::PST, NG = Cfg::NG;
     constexpr int WAVES = CS > 4 ? CS : 4;          // wavefronts per workgroup
     // One filter register set, refilled row by row, for the one-channel-per-lane shapes: it brings them
@@ -113,7 +115,6 @@ __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kerne
     // compiler's order is the faster one.
     constexpr bool FMA_BY_HAND = KPL == 1;
     static_assert(!ROLL || Cfg::rows_in_order(), "the waits on the refilled filter rows assume this order");
-    __shared__ __attribute__((aligned(16))) float lds_all[WAVES][kBlk * PST];
 
     // the wavefront index is the same in every lane: kept in a scalar register, and with it every tile coordinate
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave), lane = threadIdx.x % kWave;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kerne
     const int slot = kt_major ? seq % slots_per_xcd : seq / ktiles;
     const int tile = (xcd * slots_per_xcd + slot) * TPW + wave / CS;
     const bool valid = tile < total;                // an invalid wavefront only takes part in barriers
-    float *lds = lds_all[wave];
+    float *lds = lds_base + wave * (kBlk * PST);
 
     int t = valid ? tile : 0;
     const int tw = t % tiles_w; t /= tiles_w;
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kerne
                 for (int pp = 1; pp < CS; ++pp)
 #pragma unroll
                     for (int i = 0; i < CHUNK; ++i)
-                        acc[(c0 + i) / (TH * TW)][(c0 + i) % (TH * TW)] += lds_all[wave + pp][i * kWave + lane];
+                        acc[(c0 + i) / (TH * TW)][(c0 + i) % (TH * TW)] += lds_base[(wave + pp) * (kBlk * PST) + i * kWave + lane];
             }
         }
     }
@@ -458,47 +459,87 @@ __global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kerne
     }
 }
 
-template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD, int SU, int OFF>
-hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD = 1, int SU = 1, int OFF = 0>
+__global__ __launch_bounds__(64 * (CS > 4 ? CS : 4), MINW) void fwd_sparse_kernel(Geom g, const float *__restrict__ in,
+                                                                                  const float *__restrict__ f,
+                                                                                  float *__restrict__ out, int tiles_w,
+                                                                                  int tiles_h, int ktiles, int total,
+                                                                                  int slots_per_xcd, int kt_major)
 {
-    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
-    const int tiles_w = ceil_div(g.Wo, TW), tiles_h = ceil_div(g.Ho, TH);
-    const int ktiles = ceil_div(g.Ko, Cfg::KT);
-    const long long tiles = (long long)tiles_w * tiles_h * g.N;
+    if (form_deselected(g.sel, g.want, g.thr)) return;          // uniform over the grid, before any barrier
+    __shared__ __attribute__((aligned(16))) float lds_all[fwd_sparse_lds_floats<R, S, TH, TW, KPL, CS, SD, SU, OFF>()];
+    fwd_sparse_body<R, S, TH, TW, KPL, CS, SD, SU, OFF>(g, in, f, out, tiles_w, tiles_h, ktiles, total, slots_per_xcd, kt_major,
+                                                        lds_all);
+}
+
+// Grid of a launch with CS wavefronts per task
+struct SparseGrid {
+    int tiles_w, tiles_h, ktiles, total, slots_per_xcd, kt_major;
+    long long blocks;
+    bool ok;
+};
+
+template <int TH, int TW, int KT, int CS>
+SparseGrid sparse_grid(const Geom &g)
+{
+    SparseGrid q;
+    q.tiles_w = ceil_div(g.Wo, TW);
+    q.tiles_h = ceil_div(g.Ho, TH);
+    q.ktiles = ceil_div(g.Ko, KT);
+    const long long tiles = (long long)q.tiles_w * q.tiles_h * g.N;
     constexpr int waves = CS > 4 ? CS : 4;
     constexpr int per_wg = waves / CS;
     const long long slots = (tiles + per_wg - 1) / per_wg;             // workgroups per output-channel tile
     const long long slots_per_xcd = (slots + 7) / 8;
-    const long long blocks = slots_per_xcd * 8 * ktiles;
-    if (tiles > 0x7fffffffLL || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    q.blocks = slots_per_xcd * 8 * q.ktiles;
+    q.ok = tiles <= 0x7fffffffLL && q.blocks <= 0x7fffffffLL;
+    q.total = (int)tiles;
+    q.slots_per_xcd = (int)slots_per_xcd;
     // all filters of the layer against the 4 MB of one XCD's L2, which the input stream needs part of
-    const int kt_major = ktiles > 1 && fwd_sparse_filter_bytes(g) > kFilterBytesTileMajor;
+    q.kt_major = q.ktiles > 1 && fwd_sparse_filter_bytes(g) > kFilterBytesTileMajor;
+    return q;
+}
+
+template <int R, int S, int TH, int TW, int KPL, int MINW, int CS, int SD, int SU, int OFF>
+hipError_t launch_cs(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+{
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
+    const SparseGrid q = sparse_grid<TH, TW, Cfg::KT, CS>(g);
+    if (!q.ok) return hipErrorInvalidValue;
+    constexpr int waves = CS > 4 ? CS : 4;
     if (g.describe) {
         snprintf(g.describe, (size_t)g.describe_len, "fwd_sparse_kernel<%d, %d, %d, %d, %d, %d, %d, %d, %d, %d>", R, S, TH, TW, KPL,
                  MINW, CS, SD, SU, OFF);
         return hipSuccess;
     }
-    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS, SD, SU, OFF>), dim3((unsigned)blocks), dim3(64 * waves), 0, s,
-                       g, in, f, out, tiles_w, tiles_h, ktiles, (int)tiles, (int)slots_per_xcd, kt_major);
+    hipLaunchKernelGGL((fwd_sparse_kernel<R, S, TH, TW, KPL, MINW, CS, SD, SU, OFF>), dim3((unsigned)q.blocks), dim3(64 * waves), 0, s,
+                       g, in, f, out, q.tiles_w, q.tiles_h, q.ktiles, q.total, q.slots_per_xcd, q.kt_major);
     return hipGetLastError();
 }
 
 // Picks the channel split: layers with few tiles get 2, 4, 8 or 16 wavefronts per task so that the chip
 // (1024 SIMDs x 4 resident wavefronts) is filled and the tail is short: a wavefront walks its share
 // of the input channels one after the other, about 1.7 us per channel, so a launch that leaves
-// half the wavefront slots empty is as slow as one that fills them.
-template <int R, int S, int TH, int TW, int KPL, int MINW, int SD = 1, int SU = 1, int OFF = 0>
-hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+// half the wavefront slots empty is as slow as one that fills them.  deep = 8- and 16-way splits allowed
+// (unit-stride 3x3 only).
+inline int sparse_channel_split(const Geom &g, int TH, int TW, int KT, bool deep)
 {
-    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
-    const long long tasks = (long long)ceil_div(g.Wo, TW) * ceil_div(g.Ho, TH) * ceil_div(g.Ko, Cfg::KT) * g.N;
+    const long long tasks = (long long)ceil_div(g.Wo, TW) * ceil_div(g.Ho, TH) * ceil_div(g.Ko, KT) * g.N;
     const int CiB = g.Ci / kBlk;
-    constexpr bool deep = R == 3 && SD == 1 && SU == 1;     // 8- and 16-way splits: unit-stride 3x3 only
     int cs = 1;
     if (CiB >= 4 && CiB % 2 == 0) cs = 2;
     if ((CiB >= 16 || tasks < 3072) && CiB % 4 == 0) cs = 4;
     if (deep && tasks <= 512 && CiB % 8 == 0) cs = 8;
     if (deep && tasks <= 256 && CiB % 16 == 0) cs = 16;
+    return cs;
+}
+
+template <int R, int S, int TH, int TW, int KPL, int MINW, int SD = 1, int SU = 1, int OFF = 0>
+hipError_t launch_cfg(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)
+{
+    using Cfg = FwdSparseCfg<R, S, TH, TW, KPL, SD, SU, OFF>;
+    constexpr bool deep = R == 3 && SD == 1 && SU == 1;
+    const int cs = sparse_channel_split(g, TH, TW, Cfg::KT, deep);
     if constexpr (deep) {
         if (cs == 16) return launch_cs<R, S, TH, TW, KPL, MINW, 16, SD, SU, OFF>(g, in, f, out, s);
         if (cs == 8) return launch_cs<R, S, TH, TW, KPL, MINW, 8, SD, SU, OFF>(g, in, f, out, s);

@@ -156,7 +156,7 @@ def test_sparse_threshold_policy():
     s2 = st.ConvDesc(8, 128, 128, 56, 56, 3, 3, 2, 2, 1, 1)
     assert st.st_conv_sparse_threshold(s2, F) == 800 and st.st_conv_sparse_threshold(s2, B) == 450
     pw = st.ConvDesc(8, 64, 256, 56, 56, 1, 1)
-    assert st.st_conv_sparse_threshold(pw, F) == 900 and st.st_conv_sparse_threshold(pw, B) == 1001
+    assert st.st_conv_sparse_threshold(pw, F) == 1001 and st.st_conv_sparse_threshold(pw, B) == 1001
     # launches with few tasks split their reduction in both forms: same break-even as the large ones
     tiny = st.ConvDesc(32, 512, 512, 7, 7, 3, 3, 1, 1, 1, 1)
     assert st.st_conv_sparse_threshold(tiny, F) == 250 and st.st_conv_sparse_threshold(tiny, B) == 250

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     from tests.gpu_harness import (DeviceLayer, assert_close, check_all_passes_full,
-                                   check_all_passes_sampled, desc_of)
+                                   check_all_passes_sampled, desc_of, gather_activations, sample_coords)
     import paper_1911_10175_amd as st
 
 
@@ -303,6 +303,51 @@ def test_fwd_bwi_auto_pick_the_form_by_sparsity(p, form):
     got = L.bwi("auto")
     assert device_counts(L.auto_ws, 0) == sampled_zero_counts(st.pack_activations(dy))
     assert np.array_equal(got, L.bwi(form))
+
+
+# one geometry per instance of the main kernel that holds both forms: (tile of the zero-skipping form, wavefronts
+# per tile, tile of the dense form); minibatches large enough that the dense form does not split its channels
+COMBINED = [
+    (Geom(16, 64, 64, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<8, 8, 1, 4, 2, 8>"),
+    (Geom(16, 96, 64, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<8, 8, 1, 2, 2, 8>"),
+    (Geom(8, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 4, 4, 8>"),
+    (Geom(8, 96, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 2, 4, 8>"),
+    (Geom(28, 64, 128, 28, 28, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 4, 4, 28>"),
+    (Geom(28, 96, 128, 28, 28, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 2, 4, 28>"),
+    (Geom(96, 64, 128, 14, 14, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 4, 4, 14>"),
+    (Geom(96, 96, 128, 14, 14, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 2, 4, 14>"),
+]
+
+
+@pytest.mark.parametrize("g,kernel", COMBINED, ids=[k for _, k in COMBINED])
+def test_fwd_auto_single_main_kernel(g, kernel):
+    """st_conv_fwd_auto where one main kernel holds both forms: it is the instance expected for the
+    geometry, and with few / many zeros the result is bit-identical to the dense / zero-skipping entry
+    point's and agrees with the oracle (sampled outputs: the tensors have up to 50 M elements)."""
+    assert st.st_conv_kernel_name(desc_of(g), st.ST_PASS_FWD_AUTO) == kernel
+    for p, form in ((0.1, True), (0.7, False)):
+        x, w, _ = synth(g, p, p, seed=65)
+        L = DeviceLayer(g, x, w, None)
+        got = L.fwd("auto", raw=True)
+        assert torch.equal(got, L.fwd(form, raw=True)), f"p={p}: not the form {form!r}"
+        assert not torch.equal(got, L.fwd(not form, raw=True)), "forms indistinguishable: test is void"
+        cy = sample_coords(g.y_shape, 2048, 7)
+        ref, ref_abs = st_ref.conv_fwd_at(g, x, w, cy)
+        assert_close(gather_activations(got, cy), ref, ref_abs, f"{kernel} p={p}")
+
+
+def test_bwi_auto_single_main_kernel():
+    """The same for st_conv_bwi_auto (the kernel runs on dy with the filters transposed)."""
+    g = Geom(8, 128, 64, 56, 56, 3, 3, 1, 1, 1, 1)
+    assert st.st_conv_kernel_name(desc_of(g), st.ST_PASS_BWI_AUTO) == "fwd_auto_kernel<4, 8, 2, 4, 4, 8>"
+    for p, form in ((0.1, True), (0.7, False)):
+        x, w, dy = synth(g, p, p, seed=66)
+        L = DeviceLayer(g, None, w, dy)
+        got = L.bwi("auto", raw=True)
+        assert torch.equal(got, L.bwi(form, raw=True)), f"p={p}: not the form {form!r}"
+        cx = sample_coords(g.x_shape, 2048, 8)
+        ref, ref_abs = st_ref.conv_bwi_at(g, dy, w, cx)
+        assert_close(gather_activations(got, cx), ref, ref_abs, f"BWI auto p={p}")
 
 
 def test_fwd_bwi_auto_small_launch():
