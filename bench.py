@@ -157,11 +157,23 @@ def single_layer_config(label, layer, seed, st, stgen, torch, dev, stream, iters
     pdy = float((Ld.dy == 0).sum()) / Ld.dy.numel()
     out = {"layer": f"{L.name} {L.C}->{L.K} @{L.H} {L.R}x{L.S} N={L.N}", "zero_fraction_x": round(px, 4),
            "zero_fraction_dy": round(pdy, 4), "flops_per_pass": Ld.F}
+    d = Ld.d
+    autos = {"fwd": (st.st_conv_fwd_auto, st.ST_PASS_FWD_AUTO, lambda: (Ld.x, Ld.w, Ld.y)),
+             "bwi": (st.st_conv_bwi_auto, st.ST_PASS_BWI_AUTO, lambda: (Ld.dy, Ld.w, Ld.dx)),
+             "bww": (st.st_conv_bww_auto, st.ST_PASS_BWW_AUTO, lambda: (Ld.x, Ld.dy, Ld.dw))}
     for name, tested in (("fwd", px), ("bwi", pdy), ("bww", px)):
         s, _ = time_call(lambda: Ld.run(name, False, stream), iters, sustain_ms, stream)
         dn, _ = time_call(lambda: Ld.run(name, True, stream), iters, sustain_ms, stream)
+        # the self-selecting entry point against the faster of the two direct calls
+        fn, pa, ops = autos[name]
+        nws = st.st_conv_workspace_bytes(d, pa, False)
+        wsa = torch.empty(max(nws, 4) // 4, dtype=torch.float32, device=dev) if nws else None
+        a, b, o = ops()
+        au, _ = time_call(lambda: fn(d, a, b, o, wsa, stream), iters, sustain_ms, stream)
         out[name] = {"sparse_ms": round(s, 4), "dense_ms": round(dn, 4), "speedup": round(dn / s, 3),
-                     "effective_tflops": round(Ld.F / s / 1e9, 2)}
+                     "effective_tflops": round(Ld.F / s / 1e9, 2), "auto_ms": round(au, 4),
+                     "auto_over_faster_form": round(au / min(s, dn), 3)}
+        del wsa
     if cold:
         # rotate over enough copies of (input, output) that a launch never finds its tensors in the cache
         per_set = (Ld.x.numel() + Ld.y.numel()) * 4
@@ -220,8 +232,11 @@ def write_table1(path, st, stgen, torch, dev, stream, sustain_ms=30.0, iters=7):
                 best = min(best, ty)
                 extra = f"{ty * 1e3:.0f}"
             eff = Ld.F / ts / 1e9
+            # every tensor of the pass once: the HBM roofline of the dense control (what bounds the 1x1 layers)
+            nbytes = 4 * (Ld.x.numel() + Ld.dy.numel() + Ld.w.numel())
             rows.append(f"| {label} | {name.upper()} | {z:.2f} | {ts * 1e3:.0f} | {td * 1e3:.0f} | {ta * 1e3:.0f} | {extra} | "
-                        f"{eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | {Ld.F / td / 1e9 / PEAK_FP32_MFMA:.3f} | {td / ts:.2f} |")
+                        f"{eff:.1f} | {eff * (1 - z) / PEAK_FP32_VECTOR:.3f} | {Ld.F / td / 1e9 / PEAK_FP32_MFMA:.3f} | "
+                        f"{nbytes / td / 1e9 / PEAK_HBM_TBS:.3f} | {td / ts:.2f} | {ta / best:.2f} |")
             for k, v in enumerate((ts, td, ta, best)):
                 tot[k] += v * 1e3
         del Ld
@@ -230,9 +245,11 @@ def write_table1(path, st, stgen, torch, dev, stream, sustain_ms=30.0, iters=7):
         f.write("# Every layer of the paper's Table 1 at 50 % zeros, N=32: `python bench.py --no-cpu --no-sweep --table1 <this file>` on one MI355X\n\n"
                 "Median of 7 launches (HIP events) per entry point after 30 ms of the same launch; stgen inputs (x ReLU-shifted\n"
                 "Gaussian, dy Bernoulli-masked Gaussian, both 50 % zeros). sparse = st_conv_fwd/bwi/bww (BWW tests x),\n"
-                "auto = st_conv_*_auto, BWW(dy) = st_conv_bww_dy.\n\n")
+                "auto = st_conv_*_auto, BWW(dy) = st_conv_bww_dy; dense HBM = bytes of every tensor of the pass once / dense time /\n"
+                "8 TB/s; auto / fastest = the self-selecting entry point against the fastest direct call of the row.\n\n")
         f.write("| layer | pass | zeros of tested operand | sparse us | dense us | auto us | BWW(dy) us | effective TFLOP/s | "
-                "executed / 157.3 | dense / 157.3 (MFMA peak) | speed-up |\n|---|---|---|---|---|---|---|---|---|---|---|\n")
+                "executed / 157.3 | dense / 157.3 (MFMA peak) | dense HBM | speed-up | auto / fastest |\n"
+                "|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
         f.write("\n".join(rows) + "\n")
         f.write(f"\nSums over all rows (us): zero-skipping {tot[0]:.0f}, dense {tot[1]:.0f}, auto {tot[2]:.0f}, "
                 f"fastest form per row {tot[3]:.0f}; dense / auto = {tot[1] / tot[2]:.2f}.\n")

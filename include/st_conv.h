@@ -150,7 +150,8 @@ st_status st_conv_bww_dy(const st_conv_desc *desc, const float *x, const float *
  * average sparsity, and Sec. 5.4 names the fixed choice a limitation.  A first kernel counts the
  * zeros in a sample of x and of dy (at most 64 evenly spaced blocks of 1024 elements each); then
  * the forms above are enqueued, and those the counts do not select return at once: x is tested
- * unless dy has the strictly larger zero fraction.  Same tensors, same result, no host
+ * unless the zero fraction of dy is larger by more than 3 percentage points (at equal fractions
+ * the x-testing form is the faster one).  Same tensors, same result, no host
  * synchronisation; the cost is the sampling pass (at most 256 KB of x and of dy are read once more)
  * and the empty launches.  Where tiled kernels exist, the dense form (st_conv_bww_dense) is the
  * third candidate: it runs when even the sparser operand has fewer zeros than the measured

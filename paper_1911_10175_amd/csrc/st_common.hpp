@@ -81,13 +81,15 @@ __device__ __forceinline__ bool form_deselected(const unsigned *sel, int want, u
     return (sparse ? 0 : 1) != want;
 }
 
-// BWW form choice (st_conv_bww_auto).  dy (form 1) is tested when its zero fraction is strictly larger,
-// else x (form 0); when even the sparser operand has fewer zeros than the threshold, the dense form
-// (form 2) runs instead (threshold 0: never)
+// BWW form choice (st_conv_bww_auto).  dy (form 1) is tested when its zero fraction exceeds that of x by
+// more than 3 percentage points, else x (form 0): at equal zero fractions the form that tests dy is the
+// slower one by 1-15 % (it writes its partial sums transposed), so a tie in the samples must not pick it.
+// When even the sparser operand has fewer zeros than the threshold, the dense form (form 2) runs instead
+// (threshold 0: never)
 __device__ __forceinline__ int selected_form(const unsigned *sel)
 {
     const unsigned zx = sample_zeros(sel), nx = sample_seen(sel), zy = sample_zeros(sel + kSelDy), ny = sample_seen(sel + kSelDy);
-    const bool dy_sparser = (unsigned long long)zy * nx > (unsigned long long)zx * ny;
+    const bool dy_sparser = (unsigned long long)zy * nx * 100ull > ((unsigned long long)zx * 100ull + 3ull * nx) * ny;
     const unsigned zb = dy_sparser ? zy : zx, nb = dy_sparser ? ny : nx;
     const bool dense = (unsigned long long)zb * 1000ull < (unsigned long long)sel[kSelThr] * nb;
     return dense ? 2 : (dy_sparser ? 1 : 0);

@@ -308,8 +308,6 @@ def test_fwd_bwi_auto_pick_the_form_by_sparsity(p, form):
 # one geometry per instance of the main kernel that holds both forms: (tile of the zero-skipping form, wavefronts
 # per tile, tile of the dense form); minibatches large enough that the dense form does not split its channels
 COMBINED = [
-    (Geom(16, 64, 64, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<8, 8, 1, 4, 2, 8>"),
-    (Geom(16, 96, 64, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<8, 8, 1, 2, 2, 8>"),
     (Geom(8, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 4, 4, 8>"),
     (Geom(8, 96, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 2, 4, 8>"),
     (Geom(28, 64, 128, 28, 28, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 4, 4, 28>"),
