@@ -40,8 +40,11 @@ def draw(g: Geom, seed: int, px: float, pdy: float):
                                Geom(1, 32, 32, 11, 11, 3, 3, 2, 2, 1, 1),
                                # 9408 pixels, 64 KB filter matrix: the dense 1x1 form that keeps the filters in
                                # LDS (more dynamic LDS than the default limit) for FWD and for BWI
-                               Geom(3, 256, 64, 56, 56, 1, 1, 1, 1, 0, 0)],
-                         ids=["3x3", "1x1", "3x3s2", "1x1-filters-in-lds"])
+                               Geom(3, 256, 64, 56, 56, 1, 1, 1, 1, 0, 0),
+                               # FWD auto through the single main kernel that holds both forms (the replays see 10 %,
+                               # 60 % and 95 % zeros: both sides of the break-even), BWW auto through its merged launches
+                               Geom(8, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1)],
+                         ids=["3x3", "1x1", "3x3s2", "1x1-filters-in-lds", "3x3-single-auto-kernel"])
 def test_graph_replays_match_eager(g):
     d = desc_of(g)
     shapes = {"y": (g.N, g.K // 16, g.OH, g.OW, 16), "dx": (g.N, g.C // 16, g.H, g.W, 16),
