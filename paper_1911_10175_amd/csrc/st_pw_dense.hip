@@ -176,8 +176,11 @@ hipError_t launch_pw(const Geom &g, const float *in, const float *wd, float *out
 // for 64 -> 256 (45 and 58 us for the form this replaces).  The same kernel without its MFMAs takes 24-26 us
 // (5 TB/s, the rate of a device-to-device copy), without its stores 34.5 us: the matrix pipe at its
 // sustained rate is the longer of the two legs, and the stores of the layers that write four times what
-// they read cost another 8 us on top, because one counter tracks a wavefront's loads and stores in the
-// order issued and waiting for the next tile's input also waits for the previous tile's stores.
+// they read cost another 8 us on top.  The cause of those 8 us is not the order in which a wavefront's
+// loads and stores complete (one counter tracks both, so a wait for loaded data can end up waiting for
+// stores issued before it): a schedule in which the steps of a tile never wait behind stores (all of
+// the next tile's input requested during the current tile, one wait for everything right before the
+// stores) was measured and takes the same time.
 // Measured and dropped: 7 and 15 blocks in flight (1-6 us slower: a wavefront has only 13 to 50 steps of
 // work), four wavefronts per SIMD (4-8 us slower), filters of the next step read from LDS ahead of the
 // MFMAs (4 us slower on 64 -> 256), streaming (non-temporal) stores (12 us slower).
