@@ -255,8 +255,10 @@ def device_counts(ws, first_word):
 
 @pytest.mark.parametrize("px,pdy", [(0.2, 0.8), (0.8, 0.2), (0.0, 0.0)])
 @pytest.mark.parametrize("g", [Geom(2, 64, 128, 24, 24, 3, 3, 1, 1, 1, 1), Geom(4, 128, 64, 14, 14, 1, 1),
-                               Geom(2, 32, 32, 16, 16, 3, 3, 2, 2, 1, 1), Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2)],
-                         ids=["3x3", "1x1", "3x3s2", "5x5generic"])
+                               Geom(2, 32, 32, 16, 16, 3, 3, 2, 2, 1, 1), Geom(1, 16, 32, 9, 9, 5, 5, 1, 1, 2, 2),
+                               # one tile: every form leaves a single partial sum, which the shared final sum copies
+                               Geom(1, 16, 16, 8, 8, 3, 3, 1, 1, 1, 1)],
+                         ids=["3x3", "1x1", "3x3s2", "5x5generic", "3x3-one-tile"])
 def test_bww_auto_selects_the_sparser_operand(g, px, pdy):
     """st_conv_bww_auto: parity, and the zero counts it bases its choice on (Sec. 5.3 policy)."""
     x, w, dy = synth(g, px, pdy, seed=51)
