@@ -104,13 +104,12 @@ struct BwwSparseCfg {
 // zero-skipping kernel: tiles run over the INPUT image; LDS holds the x tile (64 channels) and
 // the dy halo of the tile (64 output channels)
 // ------------------------------------------------------------------------------------------
-template <int R, int S, int TH, int TW, int MODE = 0>
-__global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *x_in, const float *dy_in,
-                                                            float *__restrict__ part, BwwArgs B)
+// x = the tested operand, dy = the other one (the caller exchanges them for the forms that test dy).
+template <int R, int S, int TH, int TW, int MODE>
+__device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *__restrict__ x, const float *__restrict__ dy,
+                                                float *__restrict__ part)
 {
     using Cfg = BwwSparseCfg<R, S, TH, TW, MODE>;
-    const float *x = x_in, *dy = dy_in;                 // tested operand, other operand
-    if (!bww_pick(A, B, x, dy)) return;                 // uniform over the workgroup, before any barrier
     constexpr int HW = Cfg::HW, HP = Cfg::HP, TP = TH * TW;
     constexpr int CH = 8;                 // input channels per wavefront
     constexpr int GP = Cfg::GP;           // pixels per group
@@ -247,15 +246,42 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
         } else {
             // layer's block [cb: its output channels][kb: its input channels], element [ki][h*8 + ci]: the
             // lane's 8 tested channels are consecutive, the taps are reversed
+            // The values pass through an OR with a zero the compiler cannot see, i.e. through fresh registers:
+            // handed to the 16-byte stores directly, the accumulators would have to sit in aligned groups of
+            // four, and that numbering makes the multiply-adds of the main loop 6 % slower (measured), for the
+            // x-testing form as well since it is the same code.
+            const unsigned zero = (unsigned)(A.swapped - 1);
+            auto fresh = [&](float v) __attribute__((always_inline)) { return __uint_as_float(__float_as_uint(v) | zero); };
             float *p = pbase + ((size_t)cb * KB + kb) * (S * R * kBlk * kBlk) + ki * kBlk + h * CH;
 #pragma unroll
             for (int tp = 0; tp < S * R; ++tp) {
                 float4 *q = reinterpret_cast<float4 *>(p + (S * R - 1 - tp) * (kBlk * kBlk));
-                q[0] = make_float4(acc[0][tp], acc[1][tp], acc[2][tp], acc[3][tp]);
-                q[1] = make_float4(acc[4][tp], acc[5][tp], acc[6][tp], acc[7][tp]);
+                q[0] = make_float4(fresh(acc[0][tp]), fresh(acc[1][tp]), fresh(acc[2][tp]), fresh(acc[3][tp]));
+                q[1] = make_float4(fresh(acc[4][tp]), fresh(acc[5][tp]), fresh(acc[6][tp]), fresh(acc[7][tp]));
             }
         }
     }
+}
+
+template <int R, int S, int TH, int TW, int MODE = 0>
+__global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const float *__restrict__ x,
+                                                            const float *__restrict__ dy, float *__restrict__ part)
+{
+    if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
+    bww_sparse_body<R, S, TH, TW, MODE>(A, x, dy, part);
+}
+
+// st_conv_bww_auto: one launch for both zero-skipping forms of a unit-stride layer.  It carries the arguments of
+// the x-testing form (A) and of the dy-testing form (B, operands exchanged) and computes the one the sampled
+// counts select; a kernel of its own, so that the kernel of the direct calls keeps its code (with the choice
+// inside, that one ran 6 % slower).
+template <int R, int S, int TH, int TW>
+__global__ __launch_bounds__(512, 4) void bww_sparse_either_kernel(BwwArgs A, BwwArgs B, const float *x, const float *dy,
+                                                                   float *__restrict__ part)
+{
+    const float *tested = x, *other = dy;
+    if (!bww_pick(A, B, tested, other)) return;         // uniform over the workgroup, before any barrier
+    bww_sparse_body<R, S, TH, TW, 0>(A, tested, other, part);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -818,12 +844,12 @@ hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float 
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
     if (bww_s2(d)) {
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 1>), grid, dim3(512), 0, s, A, x, dy, part, A);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 1>), grid, dim3(512), 0, s, A, x, dy, part);
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A, part, dw, s);
     }
     if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s, sel);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part, A);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
@@ -872,7 +898,7 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
         A.sel = sel; A.want = 1; A.swapped = 1;
         float *part = A.splits == 1 ? dw : ws;
         dim3 grid(A.splits, ceil_div(A.K, 64) * A.cgroups);
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, part, A);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kS2TH, kS2TW, 2>), grid, dim3(512), 0, s, A, dy, x, part);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
         return reduce(d, A, part, dw, s);
@@ -883,7 +909,7 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
     A.sel = sel; A.want = 1; A.swapped = 1;
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, part, A);
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, part);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     return reduce(d, A, part, dw, s);
@@ -907,7 +933,7 @@ hipError_t launch_bww_auto_merged(const st_conv_desc &d, const float *x, const f
     A0.want = kEitherOperand; A1.want = kEitherOperand; A1.swapped = 1; A2.want = 2;
     const int ygroups = ceil_div(d.K, 64) * ceil_div(d.C, 64);      // the same for both operand roles
     dim3 grid(A0.splits > A1.splits ? A0.splits : A1.splits, ygroups);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A0, x, dy, ws, A1);
+    hipLaunchKernelGGL((bww_sparse_either_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A0, A1, x, dy, ws);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), dim3(A2.splits, ygroups), dim3(256), 0, s, A2, x, dy, ws);

@@ -67,6 +67,15 @@ __device__ __forceinline__ void static_for(F &&f)
 // the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
 
+// The zero-skipping FWD / BWI kernel with two channels per lane on unit-stride 3x3 layers keeps the two channels
+// of a lane in register pairs and reads their filters from a copy with the two side by side
+// (st_fwd_sparse_impl.hpp explains why); the kernel template and the host-side choice of the copy's layout
+// both ask here.
+constexpr bool fwd_sparse_paired(int R, int S, int KPL, int SD, int SU)
+{
+    return KPL == 2 && R == 3 && S == 3 && SD == 1 && SU == 1;
+}
+
 // Counters written by the sampling workgroups (zero_sample_block): four {zeros, elements} pairs per tensor,
 // x (or the one tested operand) in words 0..7, dy in words 8..15, the dense threshold of st_conv_bww_auto in
 // word 16.
@@ -140,6 +149,8 @@ bool fwd_sparse_supported(const Geom &g);
 // roles swapped, taps reversed); g is the geometry of the correlation the kernel runs
 size_t fwd_sparse_filter_bytes(const Geom &g);
 hipError_t launch_wave_filters(const Geom &g, bool transpose, const float *w, float *wl, hipStream_t s);
+// whether the kernel launch_fwd_sparse picks for g reads the copy with channel pairs side by side
+bool fwd_sparse_filters_paired(const Geom &g);
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *wl, float *out, hipStream_t s);
 bool fwd_dense_supported(const Geom &g);
 // the dense kernel reads filters from a reformatted copy (fwd_dense_filter_bytes) written by

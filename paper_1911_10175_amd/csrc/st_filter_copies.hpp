@@ -10,11 +10,19 @@ namespace st {
 #if defined(__HIPCC__)
 // One 16x16 filter block (kb, cb, v, u) = `block` of the LAYER's filters w (library layout) into the
 // wavefront-ordered copy wl[Ko/64][Ci][S][R][64 k] (Ko rounded up to whole groups of 64; the padding is never
-// written and never used).  TRANSPOSE selects the BWI form (channel roles exchanged, taps reversed; SparseTrain
-// Sec. 3.3).  tile: 16 x 17 floats of LDS; with TRANSPOSE every thread of the workgroup must make the call.
+// written and never used), or, with paired set, wl[Ko/128][Ci][S][R][64][2]: produced channels k and k + 64 of a
+// group of 128 side by side (Ko is then a multiple of 128).  TRANSPOSE selects the BWI form (channel roles
+// exchanged, taps reversed; SparseTrain Sec. 3.3).  tile: 32 x 17 floats of LDS; with TRANSPOSE every thread of
+// the workgroup must make the call.
+__device__ __forceinline__ size_t wave_filters_index(int ko, int ci, int tap, int Ci, int SR, int paired)
+{
+    if (paired) return ((size_t)(ko / 128) * Ci + ci) * (SR * 128) + tap * 128 + (ko % kWave) * 2 + (ko / kWave) % 2;
+    return ((size_t)(ko / kWave) * Ci + ci) * (SR * kWave) + tap * kWave + ko % kWave;
+}
+
 template <bool TRANSPOSE>
 __device__ __forceinline__ void wave_filters_block(int block, int KB, int CB, int S, int R, const float *__restrict__ w,
-                                                   float *__restrict__ wl, float (*tile)[kBlk + 1])
+                                                   float *__restrict__ wl, float (*tile)[kBlk + 1], int paired)
 {
     int t = block;
     const int u = t % R; t /= R;
@@ -22,17 +30,40 @@ __device__ __forceinline__ void wave_filters_block(int block, int KB, int CB, in
     const int cb = t % CB;
     const int kb = t / CB;
     const int a = threadIdx.x / kBlk, b = threadIdx.x % kBlk;
-    const size_t src = ((((size_t)kb * CB + cb) * S + v) * R + u) * (kBlk * kBlk);        // [ci = a][ki = b]
+    const size_t blk = (size_t)S * R * (kBlk * kBlk);
+    const size_t src = (((size_t)kb * CB + cb) * S + v) * R * (kBlk * kBlk) + (size_t)u * (kBlk * kBlk);     // [ci = a][ki = b]
     const int SR = S * R;
+    if (paired) {
+        // The block of the lower 64 channels of a group of 128 writes both partners, 8 contiguous bytes per
+        // thread; the block of the upper 64 has nothing left to do (uniform: the whole workgroup leaves).
+        // tile: 32 x 17 floats here.
+        const int pb = TRANSPOSE ? cb : kb;             // block of the produced channel
+        if (pb % 8 >= 4) return;
+        const size_t src1 = src + (TRANSPOSE ? 4 * blk : 4 * (size_t)CB * blk);      // partner: cb + 4 or kb + 4
+        float2 val;
+        if constexpr (!TRANSPOSE) {
+            const int k = kb * kBlk + b, c = cb * kBlk + a;
+            val = make_float2(w[src + a * kBlk + b], w[src1 + a * kBlk + b]);
+            *reinterpret_cast<float2 *>(wl + wave_filters_index(k, c, v * R + u, CB * kBlk, SR, 1)) = val;
+        } else {
+            tile[a][b] = w[src + a * kBlk + b];
+            tile[kBlk + a][b] = w[src1 + a * kBlk + b];
+            __syncthreads();
+            const int c = cb * kBlk + b, k = kb * kBlk + a;
+            val = make_float2(tile[b][a], tile[kBlk + b][a]);
+            *reinterpret_cast<float2 *>(wl + wave_filters_index(c, k, (S - 1 - v) * R + (R - 1 - u), KB * kBlk, SR, 1)) = val;
+        }
+        return;
+    }
     if constexpr (!TRANSPOSE) {
         const int k = kb * kBlk + b, c = cb * kBlk + a;
-        wl[((size_t)(k / kWave) * (CB * kBlk) + c) * (SR * kWave) + (v * R + u) * kWave + k % kWave] = w[src + a * kBlk + b];
+        wl[wave_filters_index(k, c, v * R + u, CB * kBlk, SR, 0)] = w[src + a * kBlk + b];
     } else {
         tile[a][b] = w[src + a * kBlk + b];
         __syncthreads();
         // produced channel = c (fast index b), reduced channel = k (a)
         const int c = cb * kBlk + b, k = kb * kBlk + a;
-        wl[((size_t)(c / kWave) * (KB * kBlk) + k) * (SR * kWave) + ((S - 1 - v) * R + (R - 1 - u)) * kWave + c % kWave] = tile[b][a];
+        wl[wave_filters_index(c, k, (S - 1 - v) * R + (R - 1 - u), KB * kBlk, SR, 0)] = tile[b][a];
     }
 }
 

@@ -53,11 +53,11 @@ namespace {
 template <bool TRANSPOSE>
 __global__ __launch_bounds__(256) void wave_filters_kernel(int KB, int CB, int S, int R,
                                                            const float *__restrict__ w, float *__restrict__ wl,
-                                                           const unsigned *sel, unsigned thr)
+                                                           const unsigned *sel, unsigned thr, int paired)
 {
     if (form_deselected(sel, 0, thr)) return;       // the copy of a form that will not run is not written
-    __shared__ float tile[kBlk][kBlk + 1];
-    wave_filters_block<TRANSPOSE>((int)blockIdx.x, KB, CB, S, R, w, wl, tile);
+    __shared__ float tile[2 * kBlk][kBlk + 1];
+    wave_filters_block<TRANSPOSE>((int)blockIdx.x, KB, CB, S, R, w, wl, tile, paired);
 }
 
 }  // namespace
@@ -72,11 +72,20 @@ hipError_t launch_wave_filters(const Geom &g, bool transpose, const float *w, fl
     const int KB = (transpose ? g.Ci : g.Ko) / kBlk, CB = (transpose ? g.Ko : g.Ci) / kBlk;     // of the layer
     const long long blocks = (long long)KB * CB * g.S * g.R;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int paired = fwd_sparse_filters_paired(g) ? 1 : 0;
     if (transpose)
-        hipLaunchKernelGGL(wave_filters_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl, g.sel, g.thr);
+        hipLaunchKernelGGL(wave_filters_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl, g.sel, g.thr,
+                           paired);
     else
-        hipLaunchKernelGGL(wave_filters_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl, g.sel, g.thr);
+        hipLaunchKernelGGL(wave_filters_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, KB, CB, g.S, g.R, w, wl, g.sel, g.thr,
+                           paired);
     return hipGetLastError();
+}
+
+// the geometries launch_fwd_sparse hands to launch_s1_k2: two channels per lane, unit-stride 3x3
+bool fwd_sparse_filters_paired(const Geom &g)
+{
+    return g.sw == 1 && g.uw == 1 && g.R == 3 && g.S == 3 && g.Ko % 128 == 0 && fwd_sparse_paired(g.R, g.S, 2, 1, 1);
 }
 
 hipError_t launch_fwd_sparse(const Geom &g, const float *in, const float *f, float *out, hipStream_t s)

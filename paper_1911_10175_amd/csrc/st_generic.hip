@@ -192,20 +192,21 @@ struct PrepareArgs {
     int KB, CB, S, R;           // filter blocks of the layer
     int Ko, Ci;                 // produced / reduced channels of the correlation the kernels run
     int transpose;              // BWI
+    int paired;                 // layout of the first copy (fwd_sparse_filters_paired)
     unsigned n_wave;            // workgroups of the first copy
     size_t total_dense;         // elements of the second copy
 };
 
 __global__ __launch_bounds__(256) void auto_prepare_kernel(PrepareArgs a)
 {
-    __shared__ float tile[kBlk][kBlk + 1];
+    __shared__ float tile[2 * kBlk][kBlk + 1];
     __shared__ unsigned red[8];
     const unsigned b = blockIdx.x;
     if (b < kSampleParts) {
         zero_sample_block(a.act, a.n_act, (int)b, a.sel, red);
     } else if (b < kSampleParts + a.n_wave) {
-        if (a.transpose) wave_filters_block<true>((int)(b - kSampleParts), a.KB, a.CB, a.S, a.R, a.w, a.wl, tile);
-        else wave_filters_block<false>((int)(b - kSampleParts), a.KB, a.CB, a.S, a.R, a.w, a.wl, tile);
+        if (a.transpose) wave_filters_block<true>((int)(b - kSampleParts), a.KB, a.CB, a.S, a.R, a.w, a.wl, tile, a.paired);
+        else wave_filters_block<false>((int)(b - kSampleParts), a.KB, a.CB, a.S, a.R, a.w, a.wl, tile, a.paired);
     } else {
         reformat_filters_block(b - kSampleParts - a.n_wave, a.Ko, a.Ci, a.S, a.R, a.transpose, a.w, a.wd, a.total_dense);
     }
@@ -283,6 +284,7 @@ hipError_t launch_auto_prepare(const Geom &g, bool transpose, const float *act, 
     a.act = act; a.n_act = n_act; a.w = w; a.wl = wl; a.wd = wd; a.sel = sel;
     a.KB = (transpose ? g.Ci : g.Ko) / kBlk; a.CB = (transpose ? g.Ko : g.Ci) / kBlk;       // of the layer
     a.S = g.S; a.R = g.R; a.Ko = g.Ko; a.Ci = g.Ci; a.transpose = transpose ? 1 : 0;
+    a.paired = fwd_sparse_filters_paired(g) ? 1 : 0;
     const long long n_wave = (long long)a.KB * a.CB * g.S * g.R;
     a.total_dense = fwd_dense_filter_bytes(g) / sizeof(float);
     const long long n_dense = (long long)((a.total_dense + 255) / 256);
