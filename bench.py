@@ -317,15 +317,16 @@ def main():
         out = torch.empty(256 * 16 * 256, dtype=torch.float32, device=dev)
         res = {}
         names = {0: "fmac_value_changes_every_instruction", 1: "fmac_same_value_first_source_x9",
-                 2: "fmac_same_value_second_source_x9", 3: "mfma_f32_32x32x2"}
+                 2: "fmac_same_value_second_source_x9", 3: "mfma_f32_32x32x2",
+                 4: "fmac_all_three_registers_even", 5: "fmac_second_factor_in_odd_registers"}
         iters = 16000
-        for pattern in (0, 1, 2, 3):
+        for pattern in (0, 1, 2, 3, 4, 5):
             for wps in (1, 2, 4):
                 wgs = 256 * wps
-                it = iters if pattern < 3 else iters // 8
+                it = iters if pattern != 3 else iters // 8
                 call = lambda: st.st_probe_issue_rate(pattern, wgs, it, out, stream)
                 med, _ = time_call(call, 7, 300.0 if (pattern, wps) == (0, 1) else 30.0, stream)
-                fl = (2.0 * 64 * 63 if pattern < 3 else 4096.0 * 4) * it * 4 * wgs
+                fl = (2.0 * 64 * 63 if pattern != 3 else 4096.0 * 4) * it * 4 * wgs
                 res[f"{names[pattern]}@{wps}_waves_per_simd"] = round(fl / med / 1e9, 1)
         print(json.dumps({"probe": "st_probe_issue_rate", "unit": "TFLOP/s", "results": res}))
         return

@@ -247,9 +247,11 @@ st_status st_conv_kernel_name(const st_conv_desc *desc, int pass, char *buf, siz
  *   pattern 1: the same with one tested-value register as FIRST source for nine instructions in a row
  *   pattern 2: the same with it as SECOND source
  *   pattern 3: 4 independent v_mfma_f32_32x32x2_f32 per iteration
+ *   pattern 4: 63 v_fmac_f32 whose accumulator and two factors all sit in even-numbered registers
+ *   pattern 5: the same accumulators and first factors with the second factor in odd-numbered registers
  * workgroups of 256 threads (4 wavefronts, one per SIMD), iters iterations each; out (device) receives one
  * float per thread, workgroups * 256 in all.  flops = 2 * 64 lanes * 63 * iters * 4 * workgroups for patterns
- * 0-2 and 4096 * 4 * iters * 4 * workgroups for pattern 3.  Asynchronous on the given stream.
+ * 0-2, 4 and 5 and 4096 * 4 * iters * 4 * workgroups for pattern 3.  Asynchronous on the given stream.
  */
 st_status st_probe_issue_rate(int pattern, int workgroups, int iters, float *out, void *hip_stream);
 

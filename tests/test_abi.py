@@ -192,5 +192,5 @@ def test_kernel_name_query():
 
 def test_probe_arguments_are_checked_on_the_host():
     assert st.st_probe_issue_rate(0, 4, 10, None, check=False) == 1
-    for bad in ((4, 4, 10), (-1, 4, 10), (0, 0, 10), (0, 4, 0), (0, (1 << 20) + 1, 1)):
+    for bad in ((6, 4, 10), (-1, 4, 10), (0, 0, 10), (0, 4, 0), (0, (1 << 20) + 1, 1)):
         assert st.st_probe_issue_rate(*bad, 256, check=False) == 2
