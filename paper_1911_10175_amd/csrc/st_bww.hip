@@ -709,9 +709,6 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
 }
 
 // 1x1 layers: chunks of kPwP pixels numbered across the minibatch; kw / cw = channels per workgroup
-#ifndef PW_DENSE_WGS
-#define PW_DENSE_WGS 512
-#endif
 BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw, int chunk = kPwP, int target = kBwwTargetWorkgroups)
 {
     BwwArgs A;
@@ -732,10 +729,11 @@ BwwArgs make_args_pw(const st_conv_desc &d, int kw, int cw, int chunk = kPwP, in
 // dense 1x1 BWW: channels of one operand per workgroup (128, or 64 for layers with no more than that), and the
 // pixels per staged chunk that go with the tile
 int pw_dense_tile(int channels) { return channels > 64 ? 128 : 64; }
+constexpr int kPwDenseWorkgroups = 512;         // two per compute unit: measured best of 256 / 512 / 1024
 BwwArgs make_args_pw_dense(const st_conv_desc &d)
 {
     const int cw = pw_dense_tile(d.C), kw = pw_dense_tile(d.K);
-    return make_args_pw(d, kw, cw, cw == 128 && kw == 128 ? 32 : 64, PW_DENSE_WGS);
+    return make_args_pw(d, kw, cw, cw == 128 && kw == 128 ? 32 : 64, kPwDenseWorkgroups);
 }
 
 int pw_kpl(const st_conv_desc &d) { return d.K % 256 == 0 ? 4 : (d.K % 128 == 0 ? 2 : 1); }
