@@ -13,6 +13,9 @@
 //    minibatch: the accumulators do not depend on the pixel, so no minibatch transposition of
 //    the layout is needed).  Each set bit costs one scalar bit test and branch; the value itself
 //    reaches all lanes through a same-address (broadcast) LDS read of the pixel's 8 channels.
+//    Which 8 of the 64 channels a wavefront takes is decided per workgroup: the channels with a non-zero in
+//    the first tile of its range are dealt round the wavefronts first (whole dead planes would otherwise
+//    leave some wavefronts idle at the barrier of every tile).
 //  * The other operand, dy at the R*S neighbouring output pixels, is a vector over the lane's
 //    output channel read from the LDS halo tile; the 3x6 window of four adjacent pixels is read
 //    once per group.
@@ -126,7 +129,6 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
     const int CB = A.C / kBlk, KB = A.K / kBlk;
     const int cbl = wave >> 1, h = wave & 1;          // channel block within the group of 64, half
     const int cb = cg * 4 + cbl;
-    const bool wave_active = cb < CB;
     const int k = kt * 64 + lane;
 
     float acc[CH][S * R];
@@ -137,6 +139,51 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
 
     const int u0 = (int)((long long)A.units * split / A.splits);
     const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
+
+    // ---- which wavefront takes which of the 64 tested channels ----
+    // ReLU leaves whole (image, channel) planes dead, and a wavefront's accumulators tie it to its 8 channels
+    // for the whole sweep: with the channels handed out in index order a tile takes as long as the wavefront
+    // that happens to hold the most alive ones.  The channels that have a non-zero in the first tile of this
+    // workgroup's range are therefore dealt round the 8 wavefronts first, the others after them: xT holds
+    // channel c at position slot_of[c], and wavefront w works on positions 8w .. 8w+7 as before.  The first
+    // tile is a prediction only (a channel that turns out alive later is computed like any other), and every
+    // accumulator still sees its pixels in the same order: the results do not depend on the assignment.
+    // With exchanged operands the order stays as it is (the 16-byte stores of that epilogue need it).
+    __shared__ unsigned alive_w[2];
+    __shared__ __attribute__((aligned(16))) unsigned char slot_of[64], chan_of[64];
+    if (threadIdx.x < 2) alive_w[threadIdx.x] = 0u;
+    __syncthreads();
+    if (!A.swapped && u0 < u1) {
+        int t = u0;
+        const int tw = t % A.tiles_w; t /= A.tiles_w;
+        const int th = t % A.tiles_h;
+        const int n = t / A.tiles_h;
+        unsigned nib = 0u;                                   // a thread's slots all have the same channel quarter
+        for (int idx = threadIdx.x; idx < TP * 16; idx += 512) {
+            const int pix = idx >> 4, q = idx & 15;
+            const int ih = th * TH + pix / TW, iw = tw * TW + pix % TW;
+            const int cbq = cg * 4 + (q >> 2);
+            if (ih < A.H && iw < A.W && cbq < CB) {
+                const float4 val = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
+                nib |= (val.x != 0.f ? 1u : 0u) | (val.y != 0.f ? 2u : 0u) | (val.z != 0.f ? 4u : 0u) | (val.w != 0.f ? 8u : 0u);
+            }
+        }
+        const int q = threadIdx.x & 15;
+        if (nib) atomicOr(&alive_w[q >> 3], nib << ((q & 7) * 4));
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const int c = threadIdx.x;
+        const unsigned long long m = ((unsigned long long)alive_w[1] << 32) | alive_w[0];
+        const unsigned long long below = (1ull << c) - 1ull;
+        const int s = (m >> c) & 1ull ? __builtin_popcountll(m & below)
+                                      : __builtin_popcountll(m) + __builtin_popcountll(~m & below);
+        const int slot = A.swapped ? c : (s & 7) * 8 + (s >> 3);
+        slot_of[c] = (unsigned char)slot;
+        chan_of[slot] = (unsigned char)c;
+    }
+    // (the barrier at the top of the tile loop orders these writes before their first use)
+    const bool wave_active = A.swapped ? cb < CB : true;
 
     // lane -> (pixel of the group, channel of the block) for the mask read
     const int mpix = lane >> 4, mch = lane & 15;
@@ -170,10 +217,30 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
             float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
             if (ih < A.H && iw < A.W && cbq < CB)
                 val = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
-            *reinterpret_cast<float4 *>(xT + pix * 64 + q * 4) = val;
+            const unsigned sl = reinterpret_cast<const unsigned *>(slot_of)[q];     // positions of channels 4q .. 4q+3
+            xT[pix * 64 + (sl & 0xffu)] = val.x;
+            xT[pix * 64 + ((sl >> 8) & 0xffu)] = val.y;
+            xT[pix * 64 + ((sl >> 16) & 0xffu)] = val.z;
+            xT[pix * 64 + (sl >> 24)] = val.w;
         }
         __syncthreads();
         if (!wave_active) continue;
+
+        // A multiply-add whose accumulator and two factors all sit in even-numbered or all in odd-numbered
+        // registers issues at half rate.  The 8 tested values of a pixel arrive in two aligned groups of four
+        // registers, channel ci in one of parity ci % 2; the accumulators of channels 2i + 1 and 2i are handed to
+        // the register allocator as (even, odd) pairs here, so that an accumulator never has the parity of
+        // its channel's tested value, wherever the window value sits.
+        typedef float f2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int ci = 0; ci < CH; ci += 2)
+#pragma unroll
+            for (int tp = 0; tp < S * R; ++tp) {
+                f2 pr = {acc[ci + 1][tp], acc[ci][tp]};
+                asm volatile("" : "+v"(pr));
+                acc[ci + 1][tp] = pr.x;
+                acc[ci][tp] = pr.y;
+            }
 
         // the mask values of a group are read one group ahead (groups follow each other in memory)
         float mnext = xT[mpix * 64 + cbl * 16 + mch];
@@ -188,8 +255,10 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
             if (g0 + GP < TP) mnext = xT[(g0 + GP + mpix) * 64 + cbl * 16 + mch];
             const unsigned long long m64 = __builtin_amdgcn_ballot_w64(mval != 0.f);
             const unsigned mlo = (unsigned)m64, mhi = (unsigned)(m64 >> 32);
-            if ((mlo | mhi) == 0u) continue;                 // nothing to do for these 4 pixels x 16 channels
             const unsigned wlo = mlo >> (h * CH), whi = mhi >> (h * CH);     // shifted once per group, not per pixel
+            // this wavefront's 8 channels of pixels 0 / 1 (wlo) and 2 / 3 (whi): bits 0-7 and 16-23
+            const unsigned any = (wlo | whi) & 0x00FF00FFu;
+            if (any == 0u) continue;                         // nothing to do for these 4 pixels x 8 channels
             // window of the other operand's halo, this lane's channel
             float dyw[WR][WC];
             const int w0 = Cfg::wrow0(a) * HW + Cfg::wcol0(b0);
@@ -238,11 +307,14 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
         const int kb = k / kBlk, ki = k % kBlk;
         float *pbase = part + (size_t)split * A.K * A.C * (S * R);
         if (!A.swapped) {
-            float *p = pbase + ((size_t)kb * CB + cb) * (S * R * kBlk * kBlk) + (h * CH) * kBlk + ki;
 #pragma unroll
-            for (int tp = 0; tp < S * R; ++tp)
+            for (int ci = 0; ci < CH; ++ci) {
+                const int c = cg * 64 + chan_of[wave * CH + ci];        // the channel this accumulator row belongs to
+                if (c >= A.C) continue;
+                float *p = pbase + ((size_t)kb * CB + c / kBlk) * (S * R * kBlk * kBlk) + (c % kBlk) * kBlk + ki;
 #pragma unroll
-                for (int ci = 0; ci < CH; ++ci) p[tp * (kBlk * kBlk) + ci * kBlk] = acc[ci][tp];
+                for (int tp = 0; tp < S * R; ++tp) p[tp * (kBlk * kBlk)] = acc[ci][tp];
+            }
         } else {
             // layer's block [cb: its output channels][kb: its input channels], element [ki][h*8 + ci]: the
             // lane's 8 tested channels are consecutive, the taps are reversed

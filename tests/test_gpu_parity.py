@@ -395,6 +395,17 @@ def test_dead_channels_are_skipped_correctly():
         x = stgen.dead_channels(x, 0.6, 75)
         dy = stgen.dead_channels(dy, 0.6, 76)
         check_all_passes_full(g2, x, w, dy, "dead-channels-2")
+    # BWW hands the channels that have a non-zero in the first tile of a workgroup's range to its wavefronts first
+    # (a prediction of the dead planes): channels that are zero in that tile and alive elsewhere, alive in that
+    # tile only, a partly filled group of 64 channels, and the same with dy as the tested operand
+    g3 = Geom(2, 144, 80, 20, 24, 3, 3, 1, 1, 1, 1)
+    x, w, dy = synth(g3, 0.3, 0.3, seed=77)
+    x = stgen.dead_channels(x, 0.7, 78)
+    dy = stgen.dead_channels(dy, 0.5, 79)
+    x[:, ::5, :8, :8] = 0.0
+    x[:, 3::7, 8:, :] = 0.0
+    x[:, 3::7, :, 8:] = 0.0
+    check_all_passes_full(g3, x, w, dy, "dead-channels-bww")
 
 
 def random_geometries(count, seed):
