@@ -198,30 +198,56 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
         const int ohs = MODE == 0 ? ih0 + A.ph - (S - 1) : MODE == 1 ? ih0 / 2 : 2 * ih0 - A.ph;
         const int ows = MODE == 0 ? iw0 + A.pw - (R - 1) : MODE == 1 ? iw0 / 2 : 2 * iw0 - A.pw;
 
-        __syncthreads();
         // dy[n, kt*64 .. +63, halo] as [pixel][64 k]; x[n, cg*64 .. +63, tile] as [pixel][64 c];
-        // 16 float4 per pixel, zeros outside the image and beyond the channel count
-        for (int idx = threadIdx.x; idx < HP * 16; idx += 512) {
+        // 16 float4 per pixel, zeros outside the image and beyond the channel count.  A thread asks for all its
+        // 16-byte pieces of the next tile at once, and before the barrier: their round trip overlaps the wait
+        // for the wavefronts still at work on the previous tile (one load, one wait, one LDS write at a time,
+        // which is what the plain loop compiles to, makes six round trips per tile).
+        constexpr int NDY = (HP * 16 + 511) / 512, NX = (TP * 16 + 511) / 512;
+        float4 sdy[NDY], sx[NX];
+        // (the slot arithmetic is redone for every tile from a thread index the compiler cannot see through:
+        // kept across the tile's work as address registers, it spills)
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+#pragma unroll
+        for (int i = 0; i < NDY; ++i) {
+            const int idx = tid + i * 512;
             const int pix = idx >> 4, q = idx & 15;
             const int oh = ohs + pix / HW, ow = ows + pix % HW;
             const int kb = kt * 4 + (q >> 2);
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (oh >= 0 && oh < A.OH && ow >= 0 && ow < A.OW && kb < KB)
-                val = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
-            *reinterpret_cast<float4 *>(dyT + pix * 64 + q * 4) = val;
+            sdy[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < HP * 16 && oh >= 0 && oh < A.OH && ow >= 0 && ow < A.OW && kb < KB)
+                sdy[i] = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
         }
-        for (int idx = threadIdx.x; idx < TP * 16; idx += 512) {
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const int idx = tid + i * 512;
             const int pix = idx >> 4, q = idx & 15;
             const int ih = ih0 + pix / TW, iw = iw0 + pix % TW;
             const int cbq = cg * 4 + (q >> 2);
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ih < A.H && iw < A.W && cbq < CB)
-                val = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
-            const unsigned sl = reinterpret_cast<const unsigned *>(slot_of)[q];     // positions of channels 4q .. 4q+3
-            xT[pix * 64 + (sl & 0xffu)] = val.x;
-            xT[pix * 64 + ((sl >> 8) & 0xffu)] = val.y;
-            xT[pix * 64 + ((sl >> 16) & 0xffu)] = val.z;
-            xT[pix * 64 + (sl >> 24)] = val.w;
+            sx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < TP * 16 && ih < A.H && iw < A.W && cbq < CB)
+                sx[i] = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
+        }
+        __syncthreads();                                     // every wavefront is done with the previous tile
+#pragma unroll
+        for (int i = 0; i < NDY; ++i) {
+            const int idx = tid + i * 512;
+            if (idx < HP * 16) *reinterpret_cast<float4 *>(dyT + idx * 4) = sdy[i];       // = [pix][q*4]
+        }
+        {
+            const unsigned sl = reinterpret_cast<const unsigned *>(slot_of)[tid & 15];     // positions of channels 4q .. 4q+3
+#pragma unroll
+            for (int i = 0; i < NX; ++i) {
+                const int idx = tid + i * 512;
+                const int pix = idx >> 4;
+                if (idx < TP * 16) {
+                    xT[pix * 64 + (sl & 0xffu)] = sx[i].x;
+                    xT[pix * 64 + ((sl >> 8) & 0xffu)] = sx[i].y;
+                    xT[pix * 64 + ((sl >> 16) & 0xffu)] = sx[i].z;
+                    xT[pix * 64 + (sl >> 24)] = sx[i].w;
+                }
+            }
         }
         __syncthreads();
         if (!wave_active) continue;
@@ -390,34 +416,64 @@ __global__ __launch_bounds__(256) void bww_dense_kernel(BwwArgs A, const float *
     const int u0 = (int)((long long)A.units * split / A.splits);
     const int u1 = (int)((long long)A.units * (split + 1) / A.splits);
 
-    for (int unit = u0; unit < u1; ++unit) {
+    // A thread's 16-byte pieces of a tile (dy tile, then x halo: 16 float4 per pixel, zeros outside the image
+    // and beyond the channel count) are asked for while the previous tile is being multiplied and written to LDS
+    // after it: the memory round trip is hidden behind the matrix work.  (A plain staging loop compiles to
+    // load, wait, write per piece: 16 round trips per tile, about as long as the tile's MFMAs.)
+    constexpr int ND = (TP * 16 + 255) / 256, NXH = (HP * 16 + 255) / 256;
+    float4 sd[ND], sx[NXH];
+    auto fetch = [&](int unit) __attribute__((always_inline)) {
         int t = unit;
         const int tw = t % A.tiles_w; t /= A.tiles_w;
         const int th = t % A.tiles_h;
         const int n = t / A.tiles_h;
         const int oh0 = th * TH, ow0 = tw * TW;
         const int ih0 = oh0 * PSTEP - A.ph, iw0 = ow0 * PSTEP - A.pw;
-
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < TP * 16; idx += 256) {
+        // (thread index the compiler cannot see through: the slot arithmetic is redone per tile instead of
+        // being kept in address registers across the tile's work)
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int idx = tid + i * 256;
             const int pix = idx >> 4, q = idx & 15;
             const int oh = oh0 + pix / TW, ow = ow0 + pix % TW;
             const int kb = kt * 4 + (q >> 2);
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (oh < A.OH && ow < A.OW && kb < KB)
-                val = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
-            *reinterpret_cast<float4 *>(dyT + pix * 64 + q * 4) = val;
+            sd[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < TP * 16 && oh < A.OH && ow < A.OW && kb < KB)
+                sd[i] = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
         }
-        for (int idx = threadIdx.x; idx < HP * 16; idx += 256) {
+#pragma unroll
+        for (int i = 0; i < NXH; ++i) {
+            const int idx = tid + i * 256;
             const int pix = idx >> 4, q = idx & 15;
             const int ih = ih0 + pix / HW, iw = iw0 + pix % HW;
             const int cb = cg * 4 + (q >> 2);
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ih >= 0 && ih < A.H && iw >= 0 && iw < A.W && cb < CB)
-                val = *reinterpret_cast<const float4 *>(x + act_off(n, cb, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
-            *reinterpret_cast<float4 *>(xT + pix * 64 + q * 4) = val;
+            sx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < HP * 16 && ih >= 0 && ih < A.H && iw >= 0 && iw < A.W && cb < CB)
+                sx[i] = *reinterpret_cast<const float4 *>(x + act_off(n, cb, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
+        }
+    };
+    if (u0 < u1) fetch(u0);
+
+    for (int unit = u0; unit < u1; ++unit) {
+        __syncthreads();                                     // every wavefront is done with the previous tile
+        {
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
+#pragma unroll
+            for (int i = 0; i < ND; ++i) {
+                const int idx = tid + i * 256;
+                if (idx < TP * 16) *reinterpret_cast<float4 *>(dyT + idx * 4) = sd[i];        // = [pix][q*4]
+            }
+#pragma unroll
+            for (int i = 0; i < NXH; ++i) {
+                const int idx = tid + i * 256;
+                if (idx < HP * 16) *reinterpret_cast<float4 *>(xT + idx * 4) = sx[i];
+            }
         }
         __syncthreads();
+        if (unit + 1 < u1) fetch(unit + 1);                  // in flight during this tile's MFMAs
 
         for (int pp = 0; pp < TP / 2; ++pp) {
             const int p = 2 * pp + half;
@@ -616,30 +672,62 @@ __global__ __launch_bounds__(512, 4) void pw_bww_sparse_kernel(BwwArgs A, const 
         while (p >= HW) { p -= HW; ++n; }
         return n < A.N;
     };
-    for (int unit = u0; unit < u1; ++unit) {
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < P * (KW / 4); idx += 512) {
+    // A thread's 16-byte pieces of a chunk (KPL of dy, one of x; zeros past the last image and beyond the channel
+    // count) are asked for while the previous chunk is worked on and written to LDS after it: with load, wait
+    // and write in turn a chunk of 32 pixels cost KPL + 1 memory round trips, more than its arithmetic.
+    constexpr int NDY = P * (KW / 4) / 512;
+    static_assert(NDY * 512 == P * (KW / 4) && P * 16 == 512, "one x piece and KPL dy pieces per thread");
+    float4 sdy[NDY], sxv;
+    auto fetch = [&]() __attribute__((always_inline)) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));                   // (slot arithmetic redone per chunk, not kept in registers)
+#pragma unroll
+        for (int i = 0; i < NDY; ++i) {
+            const int idx = tid + i * 512;
             const int pix = idx / (KW / 4), q = idx % (KW / 4);
             const int kb = kt * (KW / kBlk) + (q >> 2);
             int n, p;
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+            sdy[i] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (locate(pix, n, p) && kb < KB)
-                val = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
-            *reinterpret_cast<float4 *>(dyT + pix * KW + q * 4) = val;
+                sdy[i] = *reinterpret_cast<const float4 *>(dy + (((size_t)n * KB + kb) * HW + p) * kBlk + (q & 3) * 4);
         }
-        for (int idx = threadIdx.x; idx < P * 16; idx += 512) {
-            const int pix = idx >> 4, q = idx & 15;
+        {
+            const int pix = tid >> 4, q = tid & 15;
             const int cbq = cg * 4 + (q >> 2);
             int n, p;
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
+            sxv = make_float4(0.f, 0.f, 0.f, 0.f);
             if (locate(pix, n, p) && cbq < CB)
-                val = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cbq) * HW + p) * kBlk + (q & 3) * 4);
-            *reinterpret_cast<float4 *>(xT + pix * 64 + q * 4) = val;
+                sxv = *reinterpret_cast<const float4 *>(x + (((size_t)n * CB + cbq) * HW + p) * kBlk + (q & 3) * 4);
         }
         p0 += P;
         while (p0 >= HW) { p0 -= HW; ++n0; }
+    };
+    if (u0 < u1) fetch();
+    for (int unit = u0; unit < u1; ++unit) {
+        __syncthreads();                                // every wavefront is done with the previous chunk
+        {
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
+#pragma unroll
+            for (int i = 0; i < NDY; ++i) *reinterpret_cast<float4 *>(dyT + (tid + i * 512) * 4) = sdy[i];   // = [pix][q*4]
+            *reinterpret_cast<float4 *>(xT + tid * 4) = sxv;
+        }
         __syncthreads();
+        if (unit + 1 < u1) fetch();                     // in flight during this chunk's work
         if (!wave_active) continue;
+
+        // accumulators of channels 2i + 1 and 2i in (even, odd) register pairs, as in bww_sparse_kernel: never
+        // the parity of the channel's tested value
+        typedef float f2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int ci = 0; ci < CH; ci += 2)
+#pragma unroll
+            for (int q = 0; q < KPL; ++q) {
+                f2 pr = {acc[ci + 1][q], acc[ci][q]};
+                asm volatile("" : "+v"(pr));
+                acc[ci + 1][q] = pr.x;
+                acc[ci][q] = pr.y;
+            }
 
         float mnext = xT[mpix * 64 + cbl * 16 + mch];        // mask values are read one group ahead
         for (int g0 = 0; g0 < P; g0 += GP) {
