@@ -353,8 +353,9 @@ __device__ __forceinline__ void fwd_sparse_body(const Geom &g, const float *__re
             // time (load, wait, write) makes NST memory round trips per block of 16 channels; all at once makes
             // one but holds 4 * NST more registers at this point, the kernel's fullest.  The 4x8 tiles with two
             // channels per lane have four wavefronts per SIMD either way and gain 1-2 % at 50 % zeros, 2-4 % at
-            // 90 %; the other shapes would fall from five wavefronts to four and lose 5-11 %.
-            constexpr int NB = (PAIRED && TW == 8) ? NST : 1;
+            // 90 %, the 1x1 shapes 2-5 %; the other 3x3 shapes would fall from five wavefronts to four and
+            // lose 5-11 %.
+            constexpr int NB = ((PAIRED && TW == 8) || R * S == 1) ? NST : 1;
 #pragma unroll
             for (int j0 = 0; j0 < NST; j0 += NB) {
                 float4 sv[NB];
