@@ -228,7 +228,7 @@ int st_conv_sparse_threshold(const st_conv_desc *desc, int pass);
  * (ST_PASS_BWW) launches for this geometry, with its template arguments, as a profiler prints it (e.g.
  * "fwd_sparse_kernel<3, 3, 4, 8, 2, 4, 4, 1, 1, 0>": filter width, height, tile height, width, channels per
  * lane, wavefronts per SIMD aimed at, wavefronts sharing a tile, output stride, input spacing, input offset;
- * "bww_sparse_kernel<3, 3, 8, 8, 0>": filter width, height, tile height, width, stride mode).
+ * "bww_sparse_kernel<3, 3, 7, 8, 0>": filter width, height, tile height, width, stride mode).
  * With pass = ST_PASS_FWD_AUTO or ST_PASS_BWI_AUTO: the single main kernel of st_conv_fwd_auto /
  * st_conv_bwi_auto that holds both forms ("fwd_auto_kernel<4, 8, 2, 4, 4, 8>": tile height, width,
  * channels per lane and wavefronts per tile of the zero-skipping form, column blocks and tile width of

@@ -7,7 +7,8 @@
 //    for 4 wavefronts per SIMD; the scalar work of the zero tests of one wavefront then overlaps
 //    the vector work of the others.
 //  * The tested operand is the input x.  The tile of x for 64 input channels is staged in LDS by
-//    the workgroup (8 wavefronts = 4 channel blocks x 2 halves).  For four pixels at a time one
+//    the workgroup (8 wavefronts = 4 channel blocks x 2 halves); with unit stride both tiles are
+//    double-buffered and filled by loads that write LDS directly, one tile ahead.  For four pixels at a time one
 //    LDS read with a lane per (pixel, channel) followed by one compare and a ballot gives the
 //    non-zero mask (the vector compare of Alg. 5, along channels and pixels instead of along the
 //    minibatch: the accumulators do not depend on the pixel, so no minibatch transposition of
@@ -108,7 +109,21 @@ struct BwwSparseCfg {
 // the dy halo of the tile (64 output channels)
 // ------------------------------------------------------------------------------------------
 // x = the tested operand, dy = the other one (the caller exchanges them for the forms that test dy).
-template <int R, int S, int TH, int TW, int MODE>
+// ASYNC (unit stride): both tiles are double-buffered in dynamic LDS (bww_async_lds_bytes) and filled by loads
+// that write LDS directly, no registers in between: the tile after the current one is requested right after
+// the barrier that opens the current tile's work and lands during it, so no memory round trip is waited for
+// and a tile costs one barrier instead of two.
+typedef const __attribute__((address_space(1))) void *GlobalPtr;
+typedef __attribute__((address_space(3))) void *LdsPtr;
+static __device__ __attribute__((aligned(16))) float kZeros16[4] = {0.f, 0.f, 0.f, 0.f};     // source of padding
+template <int R, int S, int TH, int TW>
+constexpr size_t bww_async_lds_bytes()
+{
+    using Cfg = BwwSparseCfg<R, S, TH, TW, 0>;
+    return (size_t)2 * (Cfg::HP + TH * TW) * 64 * sizeof(float);
+}
+
+template <int R, int S, int TH, int TW, int MODE, bool ASYNC = false>
 __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *__restrict__ x, const float *__restrict__ dy,
                                                 float *__restrict__ part)
 {
@@ -118,9 +133,12 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
     constexpr int GP = Cfg::GP;           // pixels per group
     static_assert(TW % GP == 0, "groups must not straddle rows");
     static_assert(TH % Cfg::RU == 0, "row parities come in pairs");
+    static_assert(!ASYNC || MODE == 0, "the double-buffered form exists for unit stride only");
     constexpr int WR = Cfg::WR, WC = Cfg::WC;        // dy window of a group
-    __shared__ __attribute__((aligned(16))) float dyT[HP * 64];
-    __shared__ __attribute__((aligned(16))) float xT[TP * 64];
+    __shared__ __attribute__((aligned(16))) float dyT_static[ASYNC ? 4 : HP * 64];
+    __shared__ __attribute__((aligned(16))) float xT_static[ASYNC ? 4 : TP * 64];
+    extern __shared__ __attribute__((aligned(16))) float bww_dynamic_lds[];      // ASYNC: [2][HP + TP][64]
+    const float *dyT = dyT_static, *xT = xT_static;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int lane = threadIdx.x % kWave;
@@ -172,18 +190,72 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
         if (nib) atomicOr(&alive_w[q >> 3], nib << ((q & 7) * 4));
     }
     __syncthreads();
-    if (threadIdx.x < 64) {
-        const int c = threadIdx.x;
+    // Loads that write LDS directly put a lane's piece at lane * size: channels in index order, or one 4-byte
+    // piece per lane (measured: four times the load instructions cost 5 % of the kernel's time).  The
+    // double-buffered form therefore keeps the index order unless at least 8 of the group's channels look dead;
+    // then the workgroup stages through registers like the other forms, which can put a value anywhere for free.
+    bool dealt = !A.swapped;
+    {
         const unsigned long long m = ((unsigned long long)alive_w[1] << 32) | alive_w[0];
-        const unsigned long long below = (1ull << c) - 1ull;
-        const int s = (m >> c) & 1ull ? __builtin_popcountll(m & below)
-                                      : __builtin_popcountll(m) + __builtin_popcountll(~m & below);
-        const int slot = A.swapped ? c : (s & 7) * 8 + (s >> 3);
-        slot_of[c] = (unsigned char)slot;
-        chan_of[slot] = (unsigned char)c;
+        if constexpr (ASYNC) {
+            const int real = A.C - cg * 64 < 64 ? A.C - cg * 64 : 64;
+            const unsigned long long realmask = real == 64 ? ~0ull : (1ull << real) - 1ull;
+            dealt = dealt && __builtin_popcountll(~m & realmask) >= 8;
+        }
+        if (threadIdx.x < 64) {
+            const int c = threadIdx.x;
+            const unsigned long long below = (1ull << c) - 1ull;
+            const int s = (m >> c) & 1ull ? __builtin_popcountll(m & below)
+                                          : __builtin_popcountll(m) + __builtin_popcountll(~m & below);
+            const int slot = dealt ? (s & 7) * 8 + (s >> 3) : c;
+            slot_of[c] = (unsigned char)slot;
+            chan_of[slot] = (unsigned char)c;
+        }
     }
     // (the barrier at the top of the tile loop orders these writes before their first use)
     const bool wave_active = A.swapped ? cb < CB : true;
+
+    // ASYNC, channels in index order: request tile `unit` into buffer b, 16 bytes per lane: a wavefront's 64 pieces
+    // are 4 pixels of [pixel][64 channels].  Lanes outside the image or beyond the channel count read zeros
+    // from kZeros16; lanes beyond the buffer are switched off.  The LDS address of an instruction is the same in
+    // every lane (the hardware adds lane * size).
+    auto issue = [&](int unit, int b) __attribute__((always_inline)) {
+        int t = unit;
+        const int tw = t % A.tiles_w; t /= A.tiles_w;
+        const int th = t % A.tiles_h;
+        const int n = t / A.tiles_h;
+        const int ih0 = th * TH, iw0 = tw * TW;
+        const int ohs = ih0 + A.ph - (S - 1), ows = iw0 + A.pw - (R - 1);
+        float *dst_dy = bww_dynamic_lds + b * ((HP + TP) * 64), *dst_x = dst_dy + HP * 64;
+        int ln = lane;
+        asm volatile("" : "+v"(ln));                     // (addresses recomputed per tile, not kept in registers)
+        constexpr int NI = (HP * 16 + 63) / 64;
+        for (int i = wave; i < NI; i += 8) {
+            const int idx = i * 64 + ln;
+            const int pix = idx >> 4, q = idx & 15;
+            const int oh = ohs + pix / HW, ow = ows + pix % HW;
+            const int kb = kt * 4 + (q >> 2);
+            const float *src = kZeros16;
+            if (idx < HP * 16 && oh >= 0 && oh < A.OH && ow >= 0 && ow < A.OW && kb < KB)
+                src = dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4;
+            if (idx < HP * 16)
+                __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(dst_dy + i * 256), 16, 0, 0);
+        }
+        constexpr int NIX = TP * 16 / 64;
+        for (int i = wave; i < NIX; i += 8) {
+            const int idx = i * 64 + ln;
+            const int pix = idx >> 4, q = idx & 15;
+            const int ih = ih0 + pix / TW, iw = iw0 + pix % TW;
+            const int cbq = cg * 4 + (q >> 2);
+            const float *src = kZeros16;
+            if (ih < A.H && iw < A.W && cbq < CB) src = x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4;
+            __builtin_amdgcn_global_load_lds((GlobalPtr)src, (LdsPtr)(dst_x + i * 256), 16, 0, 0);
+        }
+    };
+    if constexpr (ASYNC) {
+        __syncthreads();                                 // the tables are written
+        if (u0 < u1 && !dealt) issue(u0, 0);
+    }
 
     // lane -> (pixel of the group, channel of the block) for the mask read
     const int mpix = lane >> 4, mch = lane & 15;
@@ -198,58 +270,72 @@ __device__ __forceinline__ void bww_sparse_body(const BwwArgs &A, const float *_
         const int ohs = MODE == 0 ? ih0 + A.ph - (S - 1) : MODE == 1 ? ih0 / 2 : 2 * ih0 - A.ph;
         const int ows = MODE == 0 ? iw0 + A.pw - (R - 1) : MODE == 1 ? iw0 / 2 : 2 * iw0 - A.pw;
 
-        // dy[n, kt*64 .. +63, halo] as [pixel][64 k]; x[n, cg*64 .. +63, tile] as [pixel][64 c];
-        // 16 float4 per pixel, zeros outside the image and beyond the channel count.  A thread asks for all its
-        // 16-byte pieces of the next tile at once, and before the barrier: their round trip overlaps the wait
-        // for the wavefronts still at work on the previous tile (one load, one wait, one LDS write at a time,
-        // which is what the plain loop compiles to, makes six round trips per tile).
-        constexpr int NDY = (HP * 16 + 511) / 512, NX = (TP * 16 + 511) / 512;
-        float4 sdy[NDY], sx[NX];
-        // (the slot arithmetic is redone for every tile from a thread index the compiler cannot see through:
-        // kept across the tile's work as address registers, it spills)
-        int tid = threadIdx.x;
-        asm volatile("" : "+v"(tid));
+        if (ASYNC && !dealt) {
+            const int b = (unit - u0) & 1;
+            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wavefront's pieces of the tile have landed
+            __syncthreads();                                 // everyone's have; everyone is done with the previous tile
+            dyT = bww_dynamic_lds + b * ((HP + TP) * 64);
+            xT = dyT + HP * 64;
+            if (unit + 1 < u1) issue(unit + 1, b ^ 1);       // lands during this tile's work
+        } else {
+            // dy[n, kt*64 .. +63, halo] as [pixel][64 k]; x[n, cg*64 .. +63, tile] as [pixel][64 c];
+            // 16 float4 per pixel, zeros outside the image and beyond the channel count.  A thread asks for all its
+            // 16-byte pieces of the next tile at once, and before the barrier: their round trip overlaps the wait
+            // for the wavefronts still at work on the previous tile (one load, one wait, one LDS write at a time,
+            // which is what the plain loop compiles to, makes six round trips per tile).
+            float *sdst_dy = ASYNC ? bww_dynamic_lds : dyT_static, *sdst_x = ASYNC ? bww_dynamic_lds + HP * 64 : xT_static;
+            if constexpr (ASYNC) {
+                dyT = sdst_dy;
+                xT = sdst_x;
+            }
+            constexpr int NDY = (HP * 16 + 511) / 512, NX = (TP * 16 + 511) / 512;
+            float4 sdy[NDY], sx[NX];
+            // (the slot arithmetic is redone for every tile from a thread index the compiler cannot see through:
+            // kept across the tile's work as address registers, it spills)
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
 #pragma unroll
-        for (int i = 0; i < NDY; ++i) {
-            const int idx = tid + i * 512;
-            const int pix = idx >> 4, q = idx & 15;
-            const int oh = ohs + pix / HW, ow = ows + pix % HW;
-            const int kb = kt * 4 + (q >> 2);
-            sdy[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx < HP * 16 && oh >= 0 && oh < A.OH && ow >= 0 && ow < A.OW && kb < KB)
-                sdy[i] = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
-        }
-#pragma unroll
-        for (int i = 0; i < NX; ++i) {
-            const int idx = tid + i * 512;
-            const int pix = idx >> 4, q = idx & 15;
-            const int ih = ih0 + pix / TW, iw = iw0 + pix % TW;
-            const int cbq = cg * 4 + (q >> 2);
-            sx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx < TP * 16 && ih < A.H && iw < A.W && cbq < CB)
-                sx[i] = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
-        }
-        __syncthreads();                                     // every wavefront is done with the previous tile
-#pragma unroll
-        for (int i = 0; i < NDY; ++i) {
-            const int idx = tid + i * 512;
-            if (idx < HP * 16) *reinterpret_cast<float4 *>(dyT + idx * 4) = sdy[i];       // = [pix][q*4]
-        }
-        {
-            const unsigned sl = reinterpret_cast<const unsigned *>(slot_of)[tid & 15];     // positions of channels 4q .. 4q+3
+            for (int i = 0; i < NDY; ++i) {
+                const int idx = tid + i * 512;
+                const int pix = idx >> 4, q = idx & 15;
+                const int oh = ohs + pix / HW, ow = ows + pix % HW;
+                const int kb = kt * 4 + (q >> 2);
+                sdy[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (idx < HP * 16 && oh >= 0 && oh < A.OH && ow >= 0 && ow < A.OW && kb < KB)
+                    sdy[i] = *reinterpret_cast<const float4 *>(dy + act_off(n, kb, oh, ow, KB, A.OH, A.OW) + (q & 3) * 4);
+            }
 #pragma unroll
             for (int i = 0; i < NX; ++i) {
                 const int idx = tid + i * 512;
-                const int pix = idx >> 4;
-                if (idx < TP * 16) {
-                    xT[pix * 64 + (sl & 0xffu)] = sx[i].x;
-                    xT[pix * 64 + ((sl >> 8) & 0xffu)] = sx[i].y;
-                    xT[pix * 64 + ((sl >> 16) & 0xffu)] = sx[i].z;
-                    xT[pix * 64 + (sl >> 24)] = sx[i].w;
+                const int pix = idx >> 4, q = idx & 15;
+                const int ih = ih0 + pix / TW, iw = iw0 + pix % TW;
+                const int cbq = cg * 4 + (q >> 2);
+                sx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (idx < TP * 16 && ih < A.H && iw < A.W && cbq < CB)
+                    sx[i] = *reinterpret_cast<const float4 *>(x + act_off(n, cbq, ih, iw, CB, A.H, A.W) + (q & 3) * 4);
+            }
+            __syncthreads();                                     // every wavefront is done with the previous tile
+#pragma unroll
+            for (int i = 0; i < NDY; ++i) {
+                const int idx = tid + i * 512;
+                if (idx < HP * 16) *reinterpret_cast<float4 *>(sdst_dy + idx * 4) = sdy[i];       // = [pix][q*4]
+            }
+            {
+                const unsigned sl = reinterpret_cast<const unsigned *>(slot_of)[tid & 15];     // positions of channels 4q .. 4q+3
+#pragma unroll
+                for (int i = 0; i < NX; ++i) {
+                    const int idx = tid + i * 512;
+                    const int pix = idx >> 4;
+                    if (idx < TP * 16) {
+                        sdst_x[pix * 64 + (sl & 0xffu)] = sx[i].x;
+                        sdst_x[pix * 64 + ((sl >> 8) & 0xffu)] = sx[i].y;
+                        sdst_x[pix * 64 + ((sl >> 16) & 0xffu)] = sx[i].z;
+                        sdst_x[pix * 64 + (sl >> 24)] = sx[i].w;
+                    }
                 }
             }
+            __syncthreads();
         }
-        __syncthreads();
         if (!wave_active) continue;
 
         // A multiply-add whose accumulator and two factors all sit in even-numbered or all in odd-numbered
@@ -366,7 +452,7 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_kernel(BwwArgs A, const flo
                                                             const float *__restrict__ dy, float *__restrict__ part)
 {
     if (deselected(A.sel, A.want)) return;              // uniform over the grid, before any barrier
-    bww_sparse_body<R, S, TH, TW, MODE>(A, x, dy, part);
+    bww_sparse_body<R, S, TH, TW, MODE, MODE == 0>(A, x, dy, part);
 }
 
 // st_conv_bww_auto: one launch for both zero-skipping forms of a unit-stride layer.  It carries the arguments of
@@ -379,7 +465,7 @@ __global__ __launch_bounds__(512, 4) void bww_sparse_either_kernel(BwwArgs A, Bw
 {
     const float *tested = x, *other = dy;
     if (!bww_pick(A, B, tested, other)) return;         // uniform over the workgroup, before any barrier
-    bww_sparse_body<R, S, TH, TW, 0>(A, tested, other, part);
+    bww_sparse_body<R, S, TH, TW, 0, true>(A, tested, other, part);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -838,7 +924,31 @@ __global__ __launch_bounds__(1024) void bww_reduce_kernel(const float4 *part, fl
 }
 
 constexpr size_t kReduceGrid = 512;          // workgroups of 1024 threads: two per compute unit
-constexpr int kSparseTH = 8, kSparseTW = 8;
+constexpr int kSparseTH = 7, kSparseTW = 8;     // unit stride: 224 ... 7 are multiples of 7; two double-buffered workgroups fit the LDS
+constexpr int kSparseS2TH = 8, kSparseS2TW = 8; // stride 2, x tested
+constexpr size_t kSparseLds = bww_async_lds_bytes<3, 3, kSparseTH, kSparseTW>();
+
+// The zero-skipping unit-stride kernels use more dynamic LDS than a kernel may without being allowed to: once per
+// device, outside any launch sequence a caller may be capturing into a graph later.
+template <class K>
+hipError_t allow_dynamic_lds(K kern, size_t bytes)
+{
+    constexpr int kMaxDev = 64;
+    static bool allowed[kMaxDev] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+    if (!allowed[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        allowed[dev] = true;
+    }
+    return hipSuccess;
+}
+BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input);
+BwwArgs sparse_args(const st_conv_desc &d);
+bool bww_s2(const st_conv_desc &d);
 constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
 // stride-2 layers: 4x8 tiles keep the strided halo of the other operand (9x17 pixels x 64 channels) in LDS
 constexpr int kS2TH = 4, kS2TW = 8;
@@ -866,6 +976,12 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
     if (splits < 1) splits = 1;
     A.splits = splits;
     return A;
+}
+
+// tiles of the zero-skipping 3x3 kernel that tests the input of layer d
+BwwArgs sparse_args(const st_conv_desc &d)
+{
+    return bww_s2(d) ? make_args(d, kSparseS2TH, kSparseS2TW, true) : make_args(d, kSparseTH, kSparseTW, true);
 }
 
 // 1x1 layers: chunks of kPwP pixels numbered across the minibatch; kw / cw = channels per workgroup
@@ -946,7 +1062,7 @@ bool bww_fast_supported(const st_conv_desc &d)
     if ((long long)ceil_div(d.K, 32) * ceil_div(d.C, 32) > 65535) return false;
     if (bww_s2(d)) return (long long)d.N * ceil_div(d.H, 4) * ceil_div(d.W, 8) <= 0x7fffffffLL;
     if (d.stride_w != 1 || d.stride_h != 1) return false;
-    const long long units = (long long)d.N * ceil_div(d.H + 2 * d.pad_h, 8) * ceil_div(d.W + 2 * d.pad_w, 16);
+    const long long units = (long long)d.N * ceil_div(d.H + 2 * d.pad_h, 7) * ceil_div(d.W + 2 * d.pad_w, 8);
     if (units > 0x7fffffffLL) return false;
     if (d.R == 3 && d.S == 3) return d.pad_w <= 2 && d.pad_h <= 2;
     if (d.R == 1 && d.S == 1)
@@ -957,7 +1073,7 @@ bool bww_fast_supported(const st_conv_desc &d)
 size_t bww_sparse_workspace(const st_conv_desc &d)
 {
     if (d.R == 1 && d.S == 1) return partial_bytes(d, make_args_pw(d, 64 * pw_kpl(d), 64));
-    return partial_bytes(d, make_args(d, kSparseTH, kSparseTW, true));       // same tiles for both strides
+    return partial_bytes(d, sparse_args(d));
 }
 
 size_t bww_dense_workspace(const st_conv_desc &d)
@@ -991,24 +1107,27 @@ hipError_t launch_pw_sparse(const st_conv_desc &d, const st_conv_desc &e, const 
 void bww_sparse_kernel_name(const st_conv_desc &d, char *buf, size_t len)
 {
     if (d.R == 1) snprintf(buf, len, "pw_bww_sparse_kernel<%d>", pw_kpl(d));
-    else snprintf(buf, len, "bww_sparse_kernel<3, 3, %d, %d, %d>", kSparseTH, kSparseTW, bww_s2(d) ? 1 : 0);
+    else if (bww_s2(d)) snprintf(buf, len, "bww_sparse_kernel<3, 3, %d, %d, 1>", kSparseS2TH, kSparseS2TW);
+    else snprintf(buf, len, "bww_sparse_kernel<3, 3, %d, %d, 0>", kSparseTH, kSparseTW);
 }
 
 hipError_t launch_bww_sparse(const st_conv_desc &d, const float *x, const float *dy, float *dw,
                              float *ws, hipStream_t s, const unsigned *sel)
 {
-    BwwArgs A = make_args(d, kSparseTH, kSparseTW, true);
+    if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s, sel);
+    BwwArgs A = sparse_args(d);
     A.sel = sel; A.want = 0;
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
     if (bww_s2(d)) {
-        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 1>), grid, dim3(512), 0, s, A, x, dy, part);
+        hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseS2TH, kSparseS2TW, 1>), grid, dim3(512), 0, s, A, x, dy, part);
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A, part, dw, s);
     }
-    if (d.R == 1) return launch_pw_sparse(d, d, x, dy, dw, ws, false, s, sel);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, x, dy, part);
-    hipError_t e = hipGetLastError();
+    hipError_t e = allow_dynamic_lds(bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 0>, kSparseLds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 0>), grid, dim3(512), kSparseLds, s, A, x, dy, part);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
 }
@@ -1067,8 +1186,10 @@ hipError_t launch_bww_sparse_dy(const st_conv_desc &d, const float *x, const flo
     A.sel = sel; A.want = 1; A.swapped = 1;
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(e.K, 64) * A.cgroups);
-    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A, dy, x, part);
-    hipError_t err = hipGetLastError();
+    hipError_t err = allow_dynamic_lds(bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 0>, kSparseLds);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((bww_sparse_kernel<3, 3, kSparseTH, kSparseTW, 0>), grid, dim3(512), kSparseLds, s, A, dy, x, part);
+    err = hipGetLastError();
     if (err != hipSuccess) return err;
     return reduce(d, A, part, dw, s);
 }
@@ -1091,8 +1212,10 @@ hipError_t launch_bww_auto_merged(const st_conv_desc &d, const float *x, const f
     A0.want = kEitherOperand; A1.want = kEitherOperand; A1.swapped = 1; A2.want = 2;
     const int ygroups = ceil_div(d.K, 64) * ceil_div(d.C, 64);      // the same for both operand roles
     dim3 grid(A0.splits > A1.splits ? A0.splits : A1.splits, ygroups);
-    hipLaunchKernelGGL((bww_sparse_either_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), 0, s, A0, A1, x, dy, ws);
-    hipError_t err = hipGetLastError();
+    hipError_t err = allow_dynamic_lds(bww_sparse_either_kernel<3, 3, kSparseTH, kSparseTW>, kSparseLds);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((bww_sparse_either_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), kSparseLds, s, A0, A1, x, dy, ws);
+    err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), dim3(A2.splits, ygroups), dim3(256), 0, s, A2, x, dy, ws);
     if ((err = hipGetLastError()) != hipSuccess) return err;

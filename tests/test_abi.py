@@ -180,7 +180,7 @@ def test_kernel_name_query():
     assert st.st_conv_kernel_name(st.ConvDesc(32, 512, 512, 28, 28, 3, 3, 1, 1, 1, 1), st.ST_PASS_FWD) == \
         "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>"
     assert st.st_conv_kernel_name(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), st.ST_PASS_FWD) is None   # generic kernel
-    assert st.st_conv_kernel_name(vgg, st.ST_PASS_BWW) == "bww_sparse_kernel<3, 3, 8, 8, 0>"
+    assert st.st_conv_kernel_name(vgg, st.ST_PASS_BWW) == "bww_sparse_kernel<3, 3, 7, 8, 0>"
     assert st.st_conv_kernel_name(st.ConvDesc(2, 64, 256, 56, 56, 1, 1), st.ST_PASS_BWW) == "pw_bww_sparse_kernel<4>"
     assert st.st_conv_kernel_name(vgg, st.ST_PASS_BWW_DY) is None
     lib = st.load_library()
