@@ -76,14 +76,14 @@ bool pick_pair(const Geom &g, Pair *p)
     // loses its fifth wavefront per SIMD and runs 14-21 % slower (measured on 64->64 @224 and the BWI of 64->128 @112)
     if (g.Ko % 128 != 0) return false;
     p->kpl = 2;
-    p->tw = (g.Wo % 8 != 0 && g.Wo % 7 == 0) ? 7 : 8;
+    p->tw = g.Wo % 7 == 0 ? 7 : 8;                 // as launch_s1_k2
     const int th = p->kpl == 2 ? 4 : 8;
     p->cs = sparse_channel_split(g, th, p->tw, 64 * p->kpl, true);
     if (p->cs != 2 && p->cs != 4) return false;
     long long blocks;
     dense_tiling(g, &p->twd, &p->kq, &blocks);
     if (p->kq != 4) return false;
-    return (p->tw == 8 && p->twd == 8) || (p->tw == 7 && (p->twd == 28 || p->twd == 14));
+    return p->twd == 8 || (p->tw == 7 && (p->twd == 28 || p->twd == 14));
 }
 
 }  // namespace
@@ -108,6 +108,10 @@ hipError_t launch_fwd_auto_combined(const Geom &g, const float *in, const float 
     if (p.tw == 8) {
         if (p.cs == 2) return launch_pair<4, 8, 2, 2, 4, 8>(g, in, wl, wd, out, s);
         return launch_pair<4, 8, 2, 4, 4, 8>(g, in, wl, wd, out, s);
+    }
+    if (p.twd == 8) {
+        if (p.cs == 2) return launch_pair<4, 7, 2, 2, 4, 8>(g, in, wl, wd, out, s);
+        return launch_pair<4, 7, 2, 4, 4, 8>(g, in, wl, wd, out, s);
     }
     if (p.twd == 28) {
         if (p.cs == 2) return launch_pair<4, 7, 2, 2, 4, 28>(g, in, wl, wd, out, s);

@@ -171,12 +171,14 @@ def test_sparse_threshold_policy():
 def test_kernel_name_query():
     """Host-side: which instance of the zero-skipping FWD / BWI kernel a geometry gets."""
     vgg = st.ConvDesc(32, 256, 256, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_kernel_name(vgg, st.ST_PASS_FWD) == "fwd_sparse_kernel<3, 3, 4, 8, 2, 4, 4, 1, 1, 0>"
+    # rows of a multiple of 7 pixels: 7-wide tiles (five wavefronts per SIMD); otherwise 8-wide
+    assert st.st_conv_kernel_name(vgg, st.ST_PASS_FWD) == "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>"
+    assert st.st_conv_kernel_name(st.ConvDesc(32, 256, 256, 64, 64, 3, 3, 1, 1, 1, 1), st.ST_PASS_FWD) == \
+        "fwd_sparse_kernel<3, 3, 4, 8, 2, 4, 4, 1, 1, 0>"
     # 64 produced channels: one channel per lane on 8x8 tiles; FWD vectorises over K, BWI over C
     mixed = st.ConvDesc(32, 64, 128, 112, 112, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_kernel_name(mixed, st.ST_PASS_FWD).startswith("fwd_sparse_kernel<3, 3, 4, 8, 2,")
+    assert st.st_conv_kernel_name(mixed, st.ST_PASS_FWD).startswith("fwd_sparse_kernel<3, 3, 4, 7, 2,")
     assert st.st_conv_kernel_name(mixed, st.ST_PASS_BWI).startswith("fwd_sparse_kernel<3, 3, 8, 8, 1,")
-    # rows of 28 pixels: 7-wide tiles
     assert st.st_conv_kernel_name(st.ConvDesc(32, 512, 512, 28, 28, 3, 3, 1, 1, 1, 1), st.ST_PASS_FWD) == \
         "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>"
     assert st.st_conv_kernel_name(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), st.ST_PASS_FWD) is None   # generic kernel

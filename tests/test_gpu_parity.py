@@ -310,8 +310,10 @@ def test_fwd_bwi_auto_pick_the_form_by_sparsity(p, form):
 # one geometry per instance of the main kernel that holds both forms: (tile of the zero-skipping form, wavefronts
 # per tile, tile of the dense form); minibatches large enough that the dense form does not split its channels
 COMBINED = [
-    (Geom(8, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 4, 4, 8>"),
-    (Geom(8, 96, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 2, 4, 8>"),
+    (Geom(8, 64, 128, 64, 48, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 4, 4, 8>"),
+    (Geom(8, 96, 128, 64, 48, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 8, 2, 2, 4, 8>"),
+    (Geom(8, 64, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 4, 4, 8>"),
+    (Geom(8, 96, 128, 56, 56, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 2, 4, 8>"),
     (Geom(28, 64, 128, 28, 28, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 4, 4, 28>"),
     (Geom(28, 96, 128, 28, 28, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 2, 4, 28>"),
     (Geom(96, 64, 128, 14, 14, 3, 3, 1, 1, 1, 1), "fwd_auto_kernel<4, 7, 2, 4, 4, 14>"),
@@ -339,7 +341,7 @@ def test_fwd_auto_single_main_kernel(g, kernel):
 def test_bwi_auto_single_main_kernel():
     """The same for st_conv_bwi_auto (the kernel runs on dy with the filters transposed)."""
     g = Geom(8, 128, 64, 56, 56, 3, 3, 1, 1, 1, 1)
-    assert st.st_conv_kernel_name(desc_of(g), st.ST_PASS_BWI_AUTO) == "fwd_auto_kernel<4, 8, 2, 4, 4, 8>"
+    assert st.st_conv_kernel_name(desc_of(g), st.ST_PASS_BWI_AUTO) == "fwd_auto_kernel<4, 7, 2, 4, 4, 8>"
     for p, form in ((0.1, True), (0.7, False)):
         x, w, dy = synth(g, p, p, seed=66)
         L = DeviceLayer(g, None, w, dy)
