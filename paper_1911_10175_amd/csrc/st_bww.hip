@@ -948,8 +948,11 @@ hipError_t allow_dynamic_lds(K kern, size_t bytes)
 }
 BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input);
 BwwArgs sparse_args(const st_conv_desc &d);
+BwwArgs dense_args(const st_conv_desc &d);
+bool dense_narrow(const st_conv_desc &d);
 bool bww_s2(const st_conv_desc &d);
 constexpr int kDenseTH = 7, kDenseTW = 14;   // 224, 112, 56, 28 and 14 are multiples of both: no ragged tiles
+constexpr int kDenseNarrowTW = 8;            // output rows of at most 8 pixels (7 x 7 layers): half of a 14-wide tile would be padding
 // stride-2 layers: 4x8 tiles keep the strided halo of the other operand (9x17 pixels x 64 channels) in LDS
 constexpr int kS2TH = 4, kS2TW = 8;
 
@@ -976,6 +979,13 @@ BwwArgs make_args(const st_conv_desc &d, int TH, int TW, bool tiles_over_input)
     if (splits < 1) splits = 1;
     A.splits = splits;
     return A;
+}
+
+// tiles of the dense unit-stride 3x3 kernel
+bool dense_narrow(const st_conv_desc &d) { return d.W + 2 * d.pad_w - d.R + 1 <= kDenseNarrowTW; }
+BwwArgs dense_args(const st_conv_desc &d)
+{
+    return make_args(d, kDenseTH, dense_narrow(d) ? kDenseNarrowTW : kDenseTW, false);
 }
 
 // tiles of the zero-skipping 3x3 kernel that tests the input of layer d
@@ -1080,7 +1090,7 @@ size_t bww_dense_workspace(const st_conv_desc &d)
 {
     if (d.R == 1 && d.S == 1) return partial_bytes(d, make_args_pw_dense(d));
     if (bww_s2(d)) return partial_bytes(d, make_args(d, kS2TH, kS2TW, false));
-    return partial_bytes(d, make_args(d, kDenseTH, kDenseTW, false));
+    return partial_bytes(d, dense_args(d));
 }
 
 namespace {
@@ -1207,7 +1217,7 @@ hipError_t launch_bww_auto_merged(const st_conv_desc &d, const float *x, const f
 {
     const st_conv_desc e = swapped_desc(d);
     BwwArgs A0 = make_args(d, kSparseTH, kSparseTW, true), A1 = make_args(e, kSparseTH, kSparseTW, true);
-    BwwArgs A2 = make_args(d, kDenseTH, kDenseTW, false);
+    BwwArgs A2 = dense_args(d);
     A0.sel = A1.sel = A2.sel = sel;
     A0.want = kEitherOperand; A1.want = kEitherOperand; A1.swapped = 1; A2.want = 2;
     const int ygroups = ceil_div(d.K, 64) * ceil_div(d.C, 64);      // the same for both operand roles
@@ -1217,7 +1227,8 @@ hipError_t launch_bww_auto_merged(const st_conv_desc &d, const float *x, const f
     hipLaunchKernelGGL((bww_sparse_either_kernel<3, 3, kSparseTH, kSparseTW>), grid, dim3(512), kSparseLds, s, A0, A1, x, dy, ws);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), dim3(A2.splits, ygroups), dim3(256), 0, s, A2, x, dy, ws);
+    if (dense_narrow(d)) hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseNarrowTW>), dim3(A2.splits, ygroups), dim3(256), 0, s, A2, x, dy, ws);
+    else hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), dim3(A2.splits, ygroups), dim3(256), 0, s, A2, x, dy, ws);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     const size_t n4 = (size_t)d.K * d.C * d.S * d.R / 4;
     const size_t nblk = (n4 + 63) / 64;
@@ -1252,11 +1263,12 @@ hipError_t launch_bww_dense(const st_conv_desc &d, const float *x, const float *
         hipError_t err = hipGetLastError();
         return err != hipSuccess ? err : reduce(d, A1, ws, dw, s);
     }
-    BwwArgs A = make_args(d, kDenseTH, kDenseTW, false);
+    BwwArgs A = dense_args(d);
     A.sel = sel; A.want = 2;
     float *part = A.splits == 1 ? dw : ws;
     dim3 grid(A.splits, ceil_div(d.K, 64) * A.cgroups);
-    hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), grid, dim3(256), 0, s, A, x, dy, part);
+    if (dense_narrow(d)) hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseNarrowTW>), grid, dim3(256), 0, s, A, x, dy, part);
+    else hipLaunchKernelGGL((bww_dense_kernel<3, 3, kDenseTH, kDenseTW>), grid, dim3(256), 0, s, A, x, dy, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return reduce(d, A, part, dw, s);
