@@ -38,10 +38,10 @@ LEVELS = (0.0, 0.3, 0.5, 0.7, 0.9)
 # run: the figure and how it was scaled are in the file named here); None until such a run exists for the kernel
 TRAFFIC_SOURCE = "profiles/vgg16_stack_step_hbm_traffic.md"
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "fwd_sparse_kernel<3, 3, 8, 8, 1, 4, 2, 1, 1, 0>": 657716393,
-    "bww_sparse_kernel<3, 3, 7, 8, 0>": 343672011,
-    "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 2, 1, 1, 0>": 332770462,
-    "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>": 215784201,
+    "fwd_sparse_kernel<3, 3, 7, 7, 1, 4, 2, 1, 1, 0>": 656477168,
+    "bww_sparse_kernel<3, 3, 7, 8, 0>": 343440616,
+    "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 2, 1, 1, 0>": 332792674,
+    "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>": 215813771,
 }
 CPU_IMAGES = 4          # images per layer the CPU oracle is timed on (of the minibatch of 32): 10-20 s of work
 

@@ -178,7 +178,8 @@ def test_kernel_name_query():
     # 64 produced channels: one channel per lane on 8x8 tiles; FWD vectorises over K, BWI over C
     mixed = st.ConvDesc(32, 64, 128, 112, 112, 3, 3, 1, 1, 1, 1)
     assert st.st_conv_kernel_name(mixed, st.ST_PASS_FWD).startswith("fwd_sparse_kernel<3, 3, 4, 7, 2,")
-    assert st.st_conv_kernel_name(mixed, st.ST_PASS_BWI).startswith("fwd_sparse_kernel<3, 3, 8, 8, 1,")
+    assert st.st_conv_kernel_name(mixed, st.ST_PASS_BWI).startswith("fwd_sparse_kernel<3, 3, 7, 7, 1,")      # sides of 7 n pixels: 7x7 tiles
+    assert st.st_conv_kernel_name(st.ConvDesc(32, 128, 64, 64, 64, 3, 3, 1, 1, 1, 1), st.ST_PASS_FWD).startswith("fwd_sparse_kernel<3, 3, 8, 8, 1,")
     assert st.st_conv_kernel_name(st.ConvDesc(32, 512, 512, 28, 28, 3, 3, 1, 1, 1, 1), st.ST_PASS_FWD) == \
         "fwd_sparse_kernel<3, 3, 4, 7, 2, 4, 4, 1, 1, 0>"
     assert st.st_conv_kernel_name(st.ConvDesc(1, 16, 16, 9, 9, 5, 5, 1, 1, 2, 2), st.ST_PASS_FWD) is None   # generic kernel
